@@ -1,0 +1,145 @@
+/*
+ * corr.h - C ABI of the MI355X correlation-lookup library (libcorr_mi355x.so).
+ *
+ * The operation is the multi-level all-pairs correlation lookup of RAFT as the
+ * paper states it (Eq. 1, Sec. "Problem and Baseline Implementation"; levels
+ * use average-pooled target features, Sec. "Efficient Correlation Volume
+ * Sampler"): for every source pixel p of fmap1, every level l < L and every
+ * integer offset (i, j) in [0, 2r]^2,
+ *
+ *   out[b, l*K*K + i*K + j, y, x] = bilinear sample of
+ *        C_l(p; v, u) = <fmap1[b,:,y,x], f2_l[b,:,v,u]> / sqrt(D)   (0 outside the level)
+ *   at  u = coords[b,0,y,x] / 2^l + (i - r),   v = coords[b,1,y,x] / 2^l + (j - r),
+ *
+ * K = 2r+1, f2_0 = fmap2, f2_l = 2x2 mean of f2_{l-1} with floor sizes.
+ * Sampling is in pixel coordinates (align_corners=True) with zero padding.
+ * Non-finite or |c| > 2^20 coordinates give zeros for that query.
+ *
+ * All pointers named "device" are HIP device pointers on the current device;
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ * Every call only enqueues work on `stream` unless stated otherwise and returns
+ * a corr_status; nothing throws across this boundary.
+ */
+#ifndef CORR_MI355X_H
+#define CORR_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct corr_pyramid corr_pyramid;   /* opaque, library-owned */
+
+typedef enum {
+    CORR_OK = 0,
+    CORR_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, empty level, mismatch with the pyramid */
+    CORR_ERR_UNSUPPORTED = -2,   /* D, L or r outside what the kernels are built for */
+    CORR_ERR_OOM = -3,           /* a device allocation failed or would not fit (see corr_full_volume_bytes) */
+    CORR_ERR_HIP = -4,           /* a HIP call or kernel launch failed */
+    CORR_ERR_MISSING_REP = -5    /* the pyramid was built without the representation this mode reads */
+} corr_status;
+
+/* How corr_sample_mode computes the lookup.  All three give the same `out`. */
+typedef enum {
+    CORR_MODE_BLOCK = 0,       /* partial block-sparse volume: queries binned by target cell, one MFMA
+                                  contraction per (cell window x query group), bilinear epilogue.
+                                  The paper's method (Sec. "Efficient Correlation Volume Sampler"). */
+    CORR_MODE_ONDEMAND = 1,    /* Eq. 1 evaluated per query, nothing stored (the paper's "on-demand"). */
+    CORR_MODE_FULLVOLUME = 2   /* dense volume of Eq. 2 + pooled volume pyramid, then sampling
+                                  (the paper's "default"); allocates corr_full_volume_bytes(). */
+} corr_mode;
+
+/* Arithmetic of the block contraction. */
+typedef enum {
+    CORR_PREC_BF16X3 = 0,   /* each fp32 feature split into bf16 hi + lo; hi*hi + hi*lo + lo*hi on bf16 MFMA,
+                               fp32 accumulate: meets the fp32 bound 1e-4 * max|C| */
+    CORR_PREC_BF16 = 1      /* hi*hi only: the paper's own precision (bf16 inputs, fp32 accumulate);
+                               bound 2e-2 * max|C| */
+} corr_precision;
+
+/* Feature representations a pyramid can hold (bit mask). */
+#define CORR_REP_SPLIT 1u   /* bf16 hi/lo, 32-channel chunk planes: read by CORR_MODE_BLOCK */
+#define CORR_REP_F32   2u   /* fp32 channels-last: read by CORR_MODE_ONDEMAND and CORR_MODE_FULLVOLUME */
+
+/*
+ * Per image pair (paper: "Input Preprocessing"): re-lays fmap1 and builds levels 0..L-1 of fmap2
+ * (2x2 mean pooling, fp32) in the representations asked for.
+ *   fmap1, fmap2 : device, dense fp32 [B, D, H, W] (NCHW); read only during the enqueued work.
+ *   *pyr         : NULL -> a pyramid is allocated (hipMalloc; synchronous) and returned;
+ *                  non-NULL -> must have been created with the same B,H,W,D,L and a superset of
+ *                  `reps`; its buffers are reused and nothing is allocated.
+ *   reps         : mask of CORR_REP_*; corr_pyramid_build uses CORR_REP_SPLIT.
+ * Limits: 1 <= L <= 4 with H >> (L-1) >= 1 and W >> (L-1) >= 1; D a multiple of 32, D <= 1024;
+ * B*H*W*81*L < 2^31.  The library owns the pyramid; free it with corr_pyramid_destroy.
+ */
+corr_status corr_pyramid_build(const float* fmap1, const float* fmap2,
+                               int B, int H, int W, int D, int L,
+                               corr_pyramid** pyr, void* stream);
+corr_status corr_pyramid_build_reps(const float* fmap1, const float* fmap2,
+                                    int B, int H, int W, int D, int L, unsigned reps,
+                                    corr_pyramid** pyr, void* stream);
+/* Synchronises the device, then frees everything the pyramid owns.  NULL is accepted. */
+corr_status corr_pyramid_destroy(corr_pyramid* pyr);
+/* Device bytes currently owned by the pyramid (features, workspace, cached dense volume). */
+size_t corr_pyramid_bytes(const corr_pyramid* pyr);
+
+/*
+ * Per lookup (paper: steps a-c of "Efficient Correlation Volume Sampler").
+ *   fmap1   : device pointer given to corr_pyramid_build for this pyramid; kept for signature
+ *             fidelity, the library reads its own re-laid copy (may be NULL).
+ *   pyr     : pyramid built for the same B,H,W,D,L.
+ *   coords  : device fp32 [B, 2, H, W]; channel 0 = x, 1 = y, absolute target position in
+ *             level-0 pixels of fmap2.
+ *   r       : lookup radius; block mode is built for r = 4, the other modes for 1 <= r <= 4.
+ *   out     : device fp32 [B, L*(2r+1)^2, H, W], fully overwritten (no need to zero it).
+ * Allocates nothing, except CORR_MODE_FULLVOLUME on its first call for a pyramid build (the dense
+ * volume, cached in the pyramid until the next build or destroy).  Work is enqueued on `stream`;
+ * calls that share a pyramid must be ordered on one stream (they share its workspace).
+ * corr_sample == corr_sample_mode(CORR_MODE_BLOCK, CORR_PREC_BF16X3, ...).
+ */
+corr_status corr_sample(const float* fmap1, corr_pyramid* pyr, const float* coords,
+                        int B, int H, int W, int D, int L, int r,
+                        float* out, void* stream);
+corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
+                             const float* fmap1, corr_pyramid* pyr, const float* coords,
+                             int B, int H, int W, int D, int L, int r,
+                             float* out, void* stream);
+
+/* Exact size of the dense volume pyramid of Eq. 2: 4 * B * (H*W) * sum_l(H_l*W_l) bytes
+ * (0 if a level is empty or L is out of range).  Pure host arithmetic. */
+size_t corr_full_volume_bytes(int B, int H, int W, int L);
+/* Device bytes corr_pyramid_build_reps would allocate for these sizes (features + workspace). */
+size_t corr_workspace_bytes(unsigned reps, int B, int H, int W, int D, int L);
+
+/*
+ * Counters of the last CORR_MODE_BLOCK call on this pyramid (written by the binning pass).
+ * Synchronises `stream` and copies them to the host.
+ *   items            work items = (target cell window, group of <= 64 queries) pairs
+ *   query_levels     B*H*W*L
+ *   null_query_levels  query-levels whose whole window lies outside the level (written as zeros)
+ *   mma_point_queries  sum over items of window points x queries padded to 16: the contraction
+ *                      work actually issued is 2*D*mma_point_queries flop per bf16 term
+ *   used_point_queries sum over items of window points x real queries
+ */
+typedef struct {
+    int64_t items;
+    int64_t query_levels;
+    int64_t null_query_levels;
+    int64_t mma_point_queries;
+    int64_t used_point_queries;
+} corr_block_stats;
+corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, void* stream);
+
+/* Host-side test hook of the binning rule (no device work): for level l and radius r, the
+ * side b of a target cell, the window side b + 2r + 1 and the number of cells per axis. */
+corr_status corr_bin_geometry(int H, int W, int l, int r, int* cell, int* window,
+                              int* cells_x, int* cells_y);
+
+const char* corr_status_string(corr_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CORR_MI355X_H */

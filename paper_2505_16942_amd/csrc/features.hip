@@ -1,0 +1,140 @@
+// Per-pair preprocessing (paper: "Input Preprocessing"; pooled target features
+// per level, Sec. "Implementation Details"): one pass over a dense NCHW fp32
+// map that emits every pyramid level in the layouts the lookup kernels read.
+//
+// A workgroup owns 32 channels x (8 rows x 32 columns) of level 0.  The tile is
+// read once (128 B runs along x), pooled 2x2 in LDS level after level
+// (0.25f * (a + b + c + d), the order of the definition, in fp32) and written as
+//   split : [B][D/32][pixel][32 x bf16 hi | 32 x bf16 lo]   (128 B per pixel)
+//   nhwc  : [B][pixel][D] fp32
+// A level-l pixel is written iff it lies inside the floor-halved level size, so
+// a trailing odd row or column is dropped exactly as the definition says.
+#include "corr_internal.h"
+
+namespace {
+
+constexpr int TILE_H = 8, TILE_W = 32, CH = CORR_CHUNK;
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+struct LevelOut {
+    uint16_t* split;   // may be null
+    float* nhwc;       // may be null
+    int H, W;
+};
+struct BuildArgs {
+    const float* src;
+    int B, D, H, W, nlev;
+    LevelOut lv[CORR_MAX_L];
+};
+
+// Write one level's part of the tile.  `t` holds [CH][rows][cols (+pad)] fp32.
+template <int ROWS, int COLS>
+__device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, int b, int kc, int D,
+                                           int y0, int x0) {
+    constexpr int PITCH = COLS + 1;
+    const int NC = D / CH;
+    // one thread = one pixel x 8 channels (16 B of hi, 16 B of lo, 32 B of fp32)
+    for (int w = threadIdx.x; w < ROWS * COLS * 4; w += blockDim.x) {
+        const int part = w & 3, pix = w >> 2;
+        const int row = pix / COLS, col = pix % COLS;
+        const int y = y0 + row, x = x0 + col;
+        if (y >= lo.H || x >= lo.W) continue;
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = t[((part * 8 + k) * ROWS + row) * PITCH + col];
+        const size_t p = (size_t)y * lo.W + x;
+        const size_t npix = (size_t)lo.H * lo.W;
+        if (lo.split) {
+            uint32_t hi[8], lw[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                hi[k] = f32_to_bf16_rne(v[k]);
+                lw[k] = f32_to_bf16_rne(v[k] - bf16_bits_to_f32(hi[k]));
+            }
+            uint16_t* dst = lo.split + (((size_t)b * NC + kc) * npix + p) * (2 * CH) + part * 8;
+            uint4 h4 = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16),
+                                  hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+            uint4 l4 = make_uint4(lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16),
+                                  lw[4] | (lw[5] << 16), lw[6] | (lw[7] << 16));
+            *reinterpret_cast<uint4*>(dst) = h4;
+            *reinterpret_cast<uint4*>(dst + CH) = l4;
+        }
+        if (lo.nhwc) {
+            float* dst = lo.nhwc + ((size_t)b * npix + p) * D + kc * CH + part * 8;
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        }
+    }
+}
+
+// dst[c][r][q] = 0.25f * (src[c][2r][2q] + src[c][2r][2q+1] + src[c][2r+1][2q] + src[c][2r+1][2q+1])
+template <int ROWS, int COLS>   // ROWS, COLS of the destination
+__device__ __forceinline__ void pool_level(const float* src, float* dst) {
+    constexpr int SP = 2 * COLS + 1, DP = COLS + 1;
+    for (int w = threadIdx.x; w < CH * ROWS * COLS; w += blockDim.x) {
+        const int c = w / (ROWS * COLS), rq = w % (ROWS * COLS);
+        const int r = rq / COLS, q = rq % COLS;
+        const float* s = src + (c * (2 * ROWS) + 2 * r) * SP + 2 * q;
+        const float a = s[0], bb = s[1], cc = s[SP], dd = s[SP + 1];
+        dst[(c * ROWS + r) * DP + q] = 0.25f * (((a + bb) + cc) + dd);
+    }
+}
+
+__global__ __launch_bounds__(256) void build_features_kernel(BuildArgs a) {
+    __shared__ float t0[CH * TILE_H * (TILE_W + 1)];
+    __shared__ float t1[CH * (TILE_H / 2) * (TILE_W / 2 + 1)];
+    __shared__ float t2[CH * (TILE_H / 4) * (TILE_W / 4 + 1)];
+    __shared__ float t3[CH * (TILE_H / 8) * (TILE_W / 8 + 1)];
+    const int NC = a.D / CH;
+    const int b = blockIdx.z / NC, kc = blockIdx.z % NC;
+    const int y0 = blockIdx.y * TILE_H, x0 = blockIdx.x * TILE_W;
+    {
+        const int col = threadIdx.x % TILE_W, row = threadIdx.x / TILE_W;
+        const int y = y0 + row, x = x0 + col;
+        const bool ok = (y < a.H) && (x < a.W);
+        const float* src = a.src + (((size_t)b * a.D + kc * CH) * a.H + (ok ? y : 0)) * a.W + (ok ? x : 0);
+        const size_t cstride = (size_t)a.H * a.W;
+#pragma unroll 8
+        for (int c = 0; c < CH; ++c)
+            t0[(c * TILE_H + row) * (TILE_W + 1) + col] = ok ? src[c * cstride] : 0.0f;
+    }
+    __syncthreads();
+    emit_level<TILE_H, TILE_W>(t0, a.lv[0], b, kc, a.D, y0, x0);
+    if (a.nlev > 1) {
+        pool_level<TILE_H / 2, TILE_W / 2>(t0, t1);
+        __syncthreads();
+        emit_level<TILE_H / 2, TILE_W / 2>(t1, a.lv[1], b, kc, a.D, y0 / 2, x0 / 2);
+    }
+    if (a.nlev > 2) {
+        pool_level<TILE_H / 4, TILE_W / 4>(t1, t2);
+        __syncthreads();
+        emit_level<TILE_H / 4, TILE_W / 4>(t2, a.lv[2], b, kc, a.D, y0 / 4, x0 / 4);
+    }
+    if (a.nlev > 3) {
+        pool_level<TILE_H / 8, TILE_W / 8>(t2, t3);
+        __syncthreads();
+        emit_level<TILE_H / 8, TILE_W / 8>(t3, a.lv[3], b, kc, a.D, y0 / 8, x0 / 8);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
+                                 uint16_t* const* split, float* const* nhwc, hipStream_t s) {
+    BuildArgs a;
+    a.src = nchw; a.B = B; a.D = D; a.H = H; a.W = W; a.nlev = nlev;
+    for (int l = 0; l < CORR_MAX_L; ++l) {
+        a.lv[l].split = (l < nlev && split) ? split[l] : nullptr;
+        a.lv[l].nhwc = (l < nlev && nhwc) ? nhwc[l] : nullptr;
+        a.lv[l].H = H >> l; a.lv[l].W = W >> l;
+    }
+    dim3 grid((W + TILE_W - 1) / TILE_W, (H + TILE_H - 1) / TILE_H, B * (D / CH));
+    hipLaunchKernelGGL(build_features_kernel, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}

@@ -1,0 +1,165 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element on the same seeded inputs.
+
+Bar (fp32 path, all three modes): max|err| <= 1e-4 * max|C|, with max|C| the
+largest magnitude in the oracle's output for that input.  bf16 mode has its
+own bound of 2e-2 * max|C|.
+"""
+import numpy as np
+import pytest
+
+from oracle import corr_oracle as oracle
+from paper_2505_16942_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+FP32_TOL = 1e-4
+BF16_TOL = 2e-2
+
+
+def _binding():
+    from paper_2505_16942_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _run(f1, f2, c, L, r, mode, prec=0, reps=3):
+    b = _binding()
+    dev = torch.device("cuda:0")
+    t1, t2, tc = (torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in (f1, f2, c))
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=reps)
+    K = 2 * r + 1
+    out = torch.full((f1.shape[0], L * K * K, f1.shape[2], f1.shape[3]), float("nan"),
+                     dtype=torch.float32, device=dev)
+    b.corr_sample(t1, pyr, tc, r=r, out=out, mode=mode, prec=prec)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    stats = b.corr_last_block_stats(pyr) if mode == b.CORR_MODE_BLOCK else None
+    pyr.destroy()
+    return res, stats
+
+
+def _check(res, ref, tol_rel, what):
+    assert res.shape == ref.shape
+    assert np.all(np.isfinite(res)), what + ": non-finite output (an element was not written?)"
+    maxc = float(np.abs(ref).max())
+    err = float(np.abs(res.astype(np.float64) - ref).max())
+    print("%s: max|err| = %.3e, max|C| = %.3f, bound = %.3e" % (what, err, maxc, tol_rel * maxc), flush=True)
+    assert err <= tol_rel * max(maxc, 1e-30), what
+
+
+SMALL = [
+    # B, H, W, D, L, flow_range
+    (1, 21, 35, 64, 3, 7.0),      # ragged vs cells, odd level sizes
+    (2, 16, 24, 32, 4, 12.0),     # batch, smallest D, level 3 is 2x3
+    (1, 8, 8, 256, 4, 3.0),       # level 3 is a single pixel
+    (1, 37, 53, 96, 2, 40.0),     # many windows partly or wholly outside
+]
+
+
+@pytest.mark.parametrize("case", SMALL)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_small_cases_all_modes(case, mode):
+    B, H, W, D, L, fr = case
+    print("case", case, "mode", mode, flush=True)
+    f1, f2, c = synth.small_case(100 + H, B, H, W, D, flow_range=fr)
+    ref = oracle.lookup(f1, f2, c, L=L, r=4)
+    res, _ = _run(f1, f2, c, L, 4, mode)
+    _check(res, ref, FP32_TOL, "small %s mode %d" % (case, mode))
+
+
+@pytest.mark.parametrize("r", [1, 2, 3])
+@pytest.mark.parametrize("mode", [1, 2])
+def test_other_radii_reference_modes(r, mode):
+    f1, f2, c = synth.small_case(7, 1, 19, 23, 64, flow_range=5.0)
+    ref = oracle.lookup(f1, f2, c, L=3, r=r)
+    res, _ = _run(f1, f2, c, 3, r, mode)
+    _check(res, ref, FP32_TOL, "r=%d mode %d" % (r, mode))
+
+
+def test_tiny_config_block_and_bf16():
+    cfg = synth.config("tiny")
+    f1, f2 = synth.features(cfg)
+    c = synth.coords(cfg)
+    ref = oracle.lookup(f1, f2, c, L=cfg["L"], r=cfg["r"])
+    res, stats = _run(f1, f2, c, cfg["L"], cfg["r"], 0, prec=0, reps=1)
+    print("stats", stats, flush=True)
+    _check(res, ref, FP32_TOL, "tiny block bf16x3")
+    assert stats["query_levels"] == 46 * 62 * 4
+    res16, _ = _run(f1, f2, c, cfg["L"], cfg["r"], 0, prec=1, reps=1)
+    _check(res16, ref, BF16_TOL, "tiny block bf16")
+    res_od, _ = _run(f1, f2, c, cfg["L"], cfg["r"], 1, reps=2)
+    _check(res_od, ref, FP32_TOL, "tiny ondemand")
+
+
+def test_special_coordinates():
+    # integer coords, non-finite, huge, exactly on borders, all outside
+    B, H, W, D, L = 1, 24, 40, 64, 4
+    f1, f2, c = synth.small_case(5, B, H, W, D, flow_range=6.0, integer_coords=True)
+    c[0, 0, 0, 0] = np.nan
+    c[0, 1, 0, 1] = np.inf
+    c[0, 0, 0, 2] = -np.inf
+    c[0, 0, 0, 3] = 3e38
+    c[0, 1, 0, 4] = -1e30
+    c[0, 0, 1, :] = -1.0
+    c[0, 0, 2, :] = W
+    c[0, 1, 3, :] = H - 1
+    c[0, 0, 4, :] = -13.0          # everything out at level 0, partly in at level 1+
+    c[0, 0, 5, :] = W + 200.0
+    c[0, 0, 6, :] = 1048576.0      # at the clamp limit
+    c[0, 0, 7, :] = 2097152.0      # beyond it
+    ref = oracle.lookup(f1, f2, c, L=L, r=4)
+    for mode in (0, 1, 2):
+        res, _ = _run(f1, f2, c, L, 4, mode)
+        _check(res, ref, FP32_TOL, "special coords mode %d" % mode)
+        assert np.all(res[0, :, 0, :5] == 0.0)
+
+
+def test_determinism_and_pyramid_reuse():
+    b = _binding()
+    dev = torch.device("cuda:0")
+    f1, f2, c = synth.small_case(9, 1, 30, 44, 128, flow_range=9.0)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    pyr = b.corr_pyramid_build(t1, t2, L=4, reps=1)
+    o1 = b.corr_sample(t1, pyr, tc).clone()
+    o2 = b.corr_sample(t1, pyr, tc).clone()
+    # rebuild into the same pyramid from different features, then back
+    b.corr_pyramid_build(t2, t1, L=4, reps=1, pyramid=pyr)
+    o3 = b.corr_sample(t2, pyr, tc).clone()
+    b.corr_pyramid_build(t1, t2, L=4, reps=1, pyramid=pyr)
+    o4 = b.corr_sample(t1, pyr, tc).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(o1, o4)
+    assert not torch.equal(o1, o3)
+    ref = oracle.lookup(f2, f1, c, L=4, r=4)
+    _check(o3.cpu().numpy(), ref, FP32_TOL, "swapped features")
+    pyr.destroy()
+
+
+def test_error_paths():
+    b = _binding()
+    dev = torch.device("cuda:0")
+    f = torch.zeros((1, 48, 16, 16), device=dev)            # D not a multiple of 32
+    with pytest.raises(b.CorrError) as e:
+        b.corr_pyramid_build(f, f, L=4)
+    assert e.value.status == b.CORR_ERR_UNSUPPORTED
+    f = torch.zeros((1, 64, 4, 16), device=dev)             # level 3 would be empty
+    with pytest.raises(b.CorrError) as e:
+        b.corr_pyramid_build(f, f, L=4)
+    assert e.value.status == b.CORR_ERR_INVALID_ARG
+    f = torch.zeros((1, 64, 16, 16), device=dev)
+    pyr = b.corr_pyramid_build(f, f, L=2, reps=1)
+    c = torch.zeros((1, 2, 16, 16), device=dev)
+    with pytest.raises(b.CorrError) as e:
+        b.corr_sample(f, pyr, c, mode=b.CORR_MODE_ONDEMAND)
+    assert e.value.status == b.CORR_ERR_MISSING_REP
+    with pytest.raises(b.CorrError) as e:
+        b.corr_sample(f, pyr, c, r=3)
+    assert e.value.status == b.CORR_ERR_UNSUPPORTED
+    pyr.destroy()
+    # the 8K dense volume is reported, not run
+    assert b.corr_full_volume_bytes(1, 540, 960, 4) == 1427549184000
+    big = b.corr_full_volume_bytes(1, 540, 960, 4)
+    free_b, _ = torch.cuda.mem_get_info()
+    assert big > free_b
