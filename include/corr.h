@@ -129,8 +129,27 @@ typedef struct {
     int64_t null_query_levels;
     int64_t mma_point_queries;
     int64_t used_point_queries;
+    /* the same, per level (entries >= L are zero); level_queries = query-levels that reached the contraction */
+    int64_t level_items[4];
+    int64_t level_mma_point_queries[4];
+    int64_t level_used_point_queries[4];
+    int64_t level_queries[4];
 } corr_block_stats;
 corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, void* stream);
+
+/*
+ * Timing hook for benchmarks.  While enabled, every CORR_MODE_BLOCK call records HIP events on its
+ * stream before the binning pass, after it, and after each level's contraction kernel (up to 256
+ * lookups between two reads; later ones are not recorded).  corr_profile_read waits for the recorded
+ * events, returns the sums of elapsed milliseconds and the number of lookups they cover, and resets.
+ */
+typedef struct {
+    int64_t lookups;
+    double binning_ms;
+    double block_ms[4];      /* contraction + epilogue kernel of level l */
+} corr_profile;
+corr_status corr_profile_enable(corr_pyramid* pyr, int enable);
+corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof);
 
 /* Host-side test hook of the binning rule (no device work): for level l and radius r, the
  * side b of a target cell, the window side b + 2r + 1 and the number of cells per axis. */

@@ -23,7 +23,8 @@ CORR_REP_SPLIT, CORR_REP_F32 = 1, 2
 EXPORTS = [
     "corr_pyramid_build", "corr_pyramid_build_reps", "corr_pyramid_destroy", "corr_pyramid_bytes",
     "corr_sample", "corr_sample_mode", "corr_full_volume_bytes", "corr_workspace_bytes",
-    "corr_last_block_stats", "corr_bin_geometry", "corr_status_string",
+    "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry",
+    "corr_status_string",
 ]
 
 
@@ -36,7 +37,13 @@ class CorrError(RuntimeError):
 class BlockStats(ctypes.Structure):
     _fields_ = [("items", ctypes.c_int64), ("query_levels", ctypes.c_int64),
                 ("null_query_levels", ctypes.c_int64), ("mma_point_queries", ctypes.c_int64),
-                ("used_point_queries", ctypes.c_int64)]
+                ("used_point_queries", ctypes.c_int64),
+                ("level_items", ctypes.c_int64 * 4), ("level_mma_point_queries", ctypes.c_int64 * 4),
+                ("level_used_point_queries", ctypes.c_int64 * 4), ("level_queries", ctypes.c_int64 * 4)]
+
+
+class Profile(ctypes.Structure):
+    _fields_ = [("lookups", ctypes.c_int64), ("binning_ms", ctypes.c_double), ("block_ms", ctypes.c_double * 4)]
 
 
 _lib = None
@@ -69,6 +76,10 @@ def load_library():
     lib.corr_workspace_bytes.restype = sz
     lib.corr_last_block_stats.argtypes = [vp, ctypes.POINTER(BlockStats), vp]
     lib.corr_last_block_stats.restype = ci
+    lib.corr_profile_enable.argtypes = [vp, ci]
+    lib.corr_profile_enable.restype = ci
+    lib.corr_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
+    lib.corr_profile_read.restype = ci
     lib.corr_bin_geometry.argtypes = [ci, ci, ci, ci] + [ctypes.POINTER(ci)] * 4
     lib.corr_bin_geometry.restype = ci
     lib.corr_status_string.argtypes = [ci]
@@ -173,4 +184,22 @@ def corr_last_block_stats(pyramid: Pyramid) -> dict:
     st = load_library().corr_last_block_stats(pyramid.handle, ctypes.byref(s), _stream())
     if st != CORR_OK:
         raise CorrError(st, "corr_last_block_stats")
-    return {k: int(getattr(s, k)) for k, _ in BlockStats._fields_}
+    out = {}
+    for k, ty in BlockStats._fields_:
+        v = getattr(s, k)
+        out[k] = int(v) if ty is ctypes.c_int64 else [int(x) for x in v]
+    return out
+
+
+def corr_profile_enable(pyramid: Pyramid, enable: bool = True) -> None:
+    st = load_library().corr_profile_enable(pyramid.handle, 1 if enable else 0)
+    if st != CORR_OK:
+        raise CorrError(st, "corr_profile_enable")
+
+
+def corr_profile_read(pyramid: Pyramid) -> dict:
+    p = Profile()
+    st = load_library().corr_profile_read(pyramid.handle, ctypes.byref(p))
+    if st != CORR_OK:
+        raise CorrError(st, "corr_profile_read")
+    return {"lookups": int(p.lookups), "binning_ms": float(p.binning_ms), "block_ms": [float(x) for x in p.block_ms]}

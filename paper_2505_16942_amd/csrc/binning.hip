@@ -30,10 +30,10 @@ struct BinArgs {
 __global__ __launch_bounds__(256) void bin_count_kernel(BinArgs a) {
     const int q = blockIdx.x * blockDim.x + threadIdx.x;   // b*HW + pixel
     const int BN = a.B * a.HW;
-    if (q >= BN) return;
-    const int b = q / a.HW, p = q - b * a.HW;
-    const float cx = a.coords[((size_t)b * 2 + 0) * a.HW + p];
-    const float cy = a.coords[((size_t)b * 2 + 1) * a.HW + p];
+    const bool real = q < BN;                 // lanes past the end stay for the shuffles
+    const int b = real ? q / a.HW : 0, p = real ? q - b * a.HW : 0;
+    const float cx = real ? a.coords[((size_t)b * 2 + 0) * a.HW + p] : NAN;
+    const float cy = real ? a.coords[((size_t)b * 2 + 1) * a.HW + p] : NAN;
     const int K = 2 * a.r + 1;
     // comparisons are false for NaN, so non-finite coordinates are "not ok"
     const bool finite_ok = (fabsf(cx) <= CORR_COORD_LIMIT) && (fabsf(cy) <= CORR_COORD_LIMIT);
@@ -51,15 +51,27 @@ __global__ __launch_bounds__(256) void bin_count_kernel(BinArgs a) {
                 bin = g.bin_base + (b * g.nby + by) * g.nbx + bx;
             }
         }
-        int rank = 0;
-        if (bin >= 0) {
-            rank = atomicAdd(&a.bin_count[bin], 1);
-        } else {
+        // Neighbouring pixels mostly fall in the same cell: one atomic per run of
+        // equal cell ids among consecutive lanes, the rest of the run takes offsets.
+        const int lane = threadIdx.x & 63;
+        const int prev = __shfl_up(bin, 1, 64);
+        const bool head = (lane == 0) || (bin != prev);
+        const unsigned long long heads = __ballot(head);
+        const unsigned long long upto = (lane == 63) ? ~0ull : ((2ull << lane) - 1ull);
+        const int head_lane = 63 - __clzll((long long)(heads & upto));
+        const unsigned long long above = heads & ~upto;
+        const int next = above ? (__ffsll((long long)above) - 1) : 64;
+        int base = 0;
+        if (head && bin >= 0) base = atomicAdd(&a.bin_count[bin], next - lane);
+        const int rank = __shfl(base, head_lane, 64) + (lane - head_lane);
+        if (bin < 0 && real) {
             float* o = a.out + ((size_t)b * a.L * K * K + (size_t)l * K * K) * a.HW + p;
             for (int t = 0; t < K * K; ++t) o[(size_t)t * a.HW] = 0.0f;
         }
-        a.q_bin[(size_t)l * BN + q] = bin;
-        a.q_rank[(size_t)l * BN + q] = rank;
+        if (real) {
+            a.q_bin[(size_t)l * BN + q] = bin;
+            a.q_rank[(size_t)l * BN + q] = rank;
+        }
     }
 }
 
@@ -75,63 +87,99 @@ struct ScanArgs {
 };
 
 // Single workgroup: exclusive scan of the counts (query offsets) and of the
-// per-cell item counts; writes the item list in cell order, hence level-major.
+// per-cell item counts, in tiles of 4096 cells (one int4 per thread, coalesced);
+// writes the item list in cell order, hence level-major.
 __global__ __launch_bounds__(1024) void bin_scan_kernel(ScanArgs a) {
-    __shared__ int s_cnt[1024], s_itm[1024];
-    __shared__ long long s_red[1024];
-    const int t = threadIdx.x;
-    const int per = (a.nbins + 1023) / 1024;
-    const int lo = t * per, hi = min(lo + per, a.nbins);
-    int csum = 0, isum = 0;
-    for (int g = lo; g < hi; ++g) {
-        const int c = a.bin_count[g];
-        csum += c;
-        isum += (c + CORR_GROUP - 1) / CORR_GROUP;
-    }
-    s_cnt[t] = csum; s_itm[t] = isum;
-    __syncthreads();
-    // Hillis-Steele inclusive scan over 1024 partials
-    for (int d = 1; d < 1024; d <<= 1) {
-        int vc = 0, vi = 0;
-        if (t >= d) { vc = s_cnt[t - d]; vi = s_itm[t - d]; }
-        __syncthreads();
-        s_cnt[t] += vc; s_itm[t] += vi;
-        __syncthreads();
-    }
-    int coff = s_cnt[t] - csum, ioff = s_itm[t] - isum;
-    long long mma = 0, used = 0;
-    for (int g = lo; g < hi; ++g) {
-        const int c = a.bin_count[g];
-        int level = 0;
-        while (level < a.L - 1 && g >= a.level_end[level]) ++level;
-        // first cell of a level records where that level's items start
-        if (g == (level == 0 ? 0 : a.level_end[level - 1])) a.level_item_off[level] = ioff;
-        a.bin_off[g] = coff;
-        a.bin_count[g] = 0;                       // ready for the next lookup
-        for (int s = 0; s < c; s += CORR_GROUP) {
-            const int n = min(CORR_GROUP, c - s);
-            a.items[ioff++] = make_int4(g, coff + s, n, level);
-            mma += (long long)a.win_pts[level] * ((n + 15) & ~15);
-            used += (long long)a.win_pts[level] * n;
+    __shared__ int s_wc[16], s_wi[16];
+    __shared__ unsigned long long s_stats[CORR_NSTATS];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    if (t < CORR_NSTATS) s_stats[t] = 0;
+    int carry_c = 0, carry_i = 0;
+    long long mma = 0, used = 0, nit = 0, nq = 0;
+    int cur = -1;
+    auto flush = [&]() {
+        if (cur >= 0 && (nit | nq)) {
+            atomicAdd(&s_stats[8 + 4 * cur + 0], (unsigned long long)nit);
+            atomicAdd(&s_stats[8 + 4 * cur + 1], (unsigned long long)mma);
+            atomicAdd(&s_stats[8 + 4 * cur + 2], (unsigned long long)used);
+            atomicAdd(&s_stats[8 + 4 * cur + 3], (unsigned long long)nq);
         }
-        coff += c;
+        mma = used = nit = nq = 0;
+    };
+    const int ntiles = (a.nbins + 4095) / 4096;
+    auto load_tile = [&](int tile) {
+        const int g0 = tile * 4096 + t * 4;
+        int4 c = make_int4(0, 0, 0, 0);
+        if (g0 + 3 < a.nbins) c = *reinterpret_cast<const int4*>(a.bin_count + g0);
+        else {
+            if (g0 < a.nbins) c.x = a.bin_count[g0];
+            if (g0 + 1 < a.nbins) c.y = a.bin_count[g0 + 1];
+            if (g0 + 2 < a.nbins) c.z = a.bin_count[g0 + 2];
+        }
+        return c;
+    };
+    int4 nxt = load_tile(0);
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int4 c4 = nxt;
+        if (tile + 1 < ntiles) nxt = load_tile(tile + 1);
+        const int c[4] = {c4.x, c4.y, c4.z, c4.w};
+        int csum = 0, isum = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { csum += c[k]; isum += (c[k] + CORR_GROUP - 1) / CORR_GROUP; }
+        int ci = csum, ii = isum;                   // inclusive scan within the wave
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int vc = __shfl_up(ci, d, 64), vi = __shfl_up(ii, d, 64);
+            if (lane >= d) { ci += vc; ii += vi; }
+        }
+        __syncthreads();                            // previous tile's s_wc/s_wi fully consumed
+        if (lane == 63) { s_wc[wave] = ci; s_wi[wave] = ii; }
+        __syncthreads();
+        int wc = 0, wi = 0, tot_c = 0, tot_i = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int vc = s_wc[w], vi = s_wi[w];
+            if (w < wave) { wc += vc; wi += vi; }
+            tot_c += vc; tot_i += vi;
+        }
+        int coff = carry_c + wc + ci - csum, ioff = carry_i + wi + ii - isum;
+        carry_c += tot_c; carry_i += tot_i;
+        const int g0 = tile * 4096 + t * 4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int g = g0 + k;
+            if (g >= a.nbins) break;
+            int level = 0;
+            while (level < a.L - 1 && g >= a.level_end[level]) ++level;
+            if (level != cur) { flush(); cur = level; }
+            nq += c[k];
+            // first cell of a level records where that level's items start
+            if (g == (level == 0 ? 0 : a.level_end[level - 1])) a.level_item_off[level] = ioff;
+            a.bin_off[g] = coff;
+            a.bin_count[g] = 0;                     // ready for the next lookup
+            for (int s = 0; s < c[k]; s += CORR_GROUP) {
+                const int n = min(CORR_GROUP, c[k] - s);
+                a.items[ioff++] = make_int4(g, coff + s, n, level);
+                ++nit;
+                mma += (long long)a.win_pts[level] * ((n + 15) & ~15);
+                used += (long long)a.win_pts[level] * n;
+            }
+            coff += c[k];
+        }
     }
-    s_red[t] = mma;
+    flush();
     __syncthreads();
-    for (int d = 512; d > 0; d >>= 1) { if (t < d) s_red[t] += s_red[t + d]; __syncthreads(); }
-    const long long mma_all = s_red[0];
-    __syncthreads();
-    s_red[t] = used;
-    __syncthreads();
-    for (int d = 512; d > 0; d >>= 1) { if (t < d) s_red[t] += s_red[t + d]; __syncthreads(); }
-    if (t == 1023) {
-        a.level_item_off[a.L] = s_itm[1023];
-        a.stats[0] = s_itm[1023];                               // items
+    if (t == 0) {
+        a.level_item_off[a.L] = carry_i;
+        long long mma_all = 0, used_all = 0;
+        for (int l = 0; l < CORR_MAX_L; ++l) { mma_all += s_stats[8 + 4 * l + 1]; used_all += s_stats[8 + 4 * l + 2]; }
+        a.stats[0] = carry_i;                                   // items
         a.stats[1] = (long long)a.BN * a.L;                     // query-levels
-        a.stats[2] = (long long)a.BN * a.L - s_cnt[1023];       // null query-levels
+        a.stats[2] = (long long)a.BN * a.L - carry_c;           // null query-levels
         a.stats[3] = mma_all;
-        a.stats[4] = s_red[0];
+        a.stats[4] = used_all;
     }
+    if (t >= 8 && t < CORR_NSTATS) a.stats[t] = (long long)s_stats[t];
 }
 
 __global__ __launch_bounds__(256) void bin_scatter_kernel(const int* __restrict__ q_bin,

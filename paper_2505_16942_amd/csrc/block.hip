@@ -135,16 +135,22 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
     const int nqf = (n + 15) >> 4;
     const int frag_off = (lane & 15) * ROWB + (lane >> 4) * 16;
 
-    for (int kc = 0; kc < a.NC; ++kc) {
+    // global -> registers for chunk 0; inside the loop the next chunk's loads are
+    // issued right after the LDS stores so that they fly under the MFMAs
+    uint4 wv[G::WIN_ITERS], qv[2];
+    auto load_chunk = [&](int kc) {
         const uint16_t* f2c = a.f2s + ((size_t)b * a.NC + kc) * (size_t)HWl * 64;
         const uint16_t* f1c = a.f1s + ((size_t)b * a.NC + kc) * (size_t)a.HW * 64;
-        uint4 wv[G::WIN_ITERS], qv[2];
 #pragma unroll
         for (int it = 0; it < G::WIN_ITERS; ++it)
             wv[it] = goff[it] >= 0 ? *reinterpret_cast<const uint4*>(f2c + goff[it]) : make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int it = 0; it < 2; ++it)
             qv[it] = qoff[it] >= 0 ? *reinterpret_cast<const uint4*>(f1c + qoff[it]) : make_uint4(0, 0, 0, 0);
+    };
+    load_chunk(0);
+
+    for (int kc = 0; kc < a.NC; ++kc) {
         if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk
 #pragma unroll
         for (int it = 0; it < G::WIN_ITERS; ++it) {
@@ -158,6 +164,7 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
             *reinterpret_cast<uint4*>(qry + (idx >> 3) * ROWB + (idx & 7) * 16) = qv[it];
         }
         __syncthreads();
+        if (kc + 1 < a.NC) load_chunk(kc + 1);
 
         bf16x8 qh[4], ql[4];
 #pragma unroll
@@ -238,7 +245,8 @@ hipError_t launch_level(const BlockArgs& a, int max_items, hipStream_t s) {
 }
 
 template <bool THREE>
-hipError_t launch_all_levels(corr_pyramid* p, const float* coords, float* out, hipStream_t s) {
+hipError_t launch_all_levels(corr_pyramid* p, const float* coords, float* out, hipStream_t s,
+                             hipEvent_t* level_done) {
     const int HW = p->H * p->W, BN = p->B * HW;
     for (int l = 0; l < p->L; ++l) {
         BlockArgs a;
@@ -256,6 +264,7 @@ hipError_t launch_all_levels(corr_pyramid* p, const float* coords, float* out, h
             case 1: e = launch_level<1, 4, THREE>(a, max_items, s); break;
             default: e = launch_level<0, 4, THREE>(a, max_items, s); break;
         }
+        if (e == hipSuccess && level_done) e = hipEventRecord(level_done[l], s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -263,8 +272,9 @@ hipError_t launch_all_levels(corr_pyramid* p, const float* coords, float* out, h
 
 }  // namespace
 
-hipError_t launch_block(corr_pyramid* p, const float* coords, int r, int prec, float* out, hipStream_t s) {
+hipError_t launch_block(corr_pyramid* p, const float* coords, int r, int prec, float* out, hipStream_t s,
+                        hipEvent_t* level_done) {
     (void)r;   // built for r = 4; the caller has checked
-    return prec == CORR_PREC_BF16 ? launch_all_levels<false>(p, coords, out, s)
-                                  : launch_all_levels<true>(p, coords, out, s);
+    return prec == CORR_PREC_BF16 ? launch_all_levels<false>(p, coords, out, s, level_done)
+                                  : launch_all_levels<true>(p, coords, out, s, level_done);
 }

@@ -39,8 +39,6 @@ void fill_geometry(corr_pyramid* p, int r) {
     p->max_items = items;
 }
 
-struct Plan { size_t bytes; };
-
 template <typename T>
 corr_status dev_alloc(T** ptr, size_t count, size_t* total) {
     void* v = nullptr;
@@ -66,6 +64,10 @@ void free_all(corr_pyramid* p) {
     (void)hipFree(p->f1_nhwc); (void)hipFree(p->f1_split);
     for (int l = 0; l < CORR_MAX_L; ++l) { (void)hipFree(p->f2_nhwc[l]); (void)hipFree(p->f2_split[l]); }
     (void)hipFree(p->bin_count); (void)hipFree(p->bin_off); (void)hipFree(p->q_bin); (void)hipFree(p->q_rank);
+    if (p->prof_ev) {
+        for (int i = 0; i < CORR_PROF_LOOKUPS * (p->L + 2); ++i) (void)hipEventDestroy(p->prof_ev[i]);
+        delete[] p->prof_ev;
+    }
     (void)hipFree(p->perm); (void)hipFree(p->items); (void)hipFree(p->level_item_off); (void)hipFree(p->stats);
     delete p;
 }
@@ -104,10 +106,10 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
         need(dev_alloc(&p->perm, BN * L, &p->bytes));
         need(dev_alloc(&p->items, (size_t)p->max_items, &p->bytes));
         need(dev_alloc(&p->level_item_off, (size_t)CORR_MAX_L + 1, &p->bytes));
-        need(dev_alloc(&p->stats, (size_t)8, &p->bytes));
+        need(dev_alloc(&p->stats, (size_t)CORR_NSTATS, &p->bytes));
         if (st == CORR_OK) {
             if (hipMemset(p->bin_count, 0, sizeof(int) * p->nbins) != hipSuccess ||
-                hipMemset(p->stats, 0, sizeof(long long) * 8) != hipSuccess ||
+                hipMemset(p->stats, 0, sizeof(long long) * CORR_NSTATS) != hipSuccess ||
                 hipMemset(p->level_item_off, 0, sizeof(int) * (CORR_MAX_L + 1)) != hipSuccess)
                 st = CORR_ERR_HIP;
         }
@@ -233,8 +235,14 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec, const float* f
             if (prec != CORR_PREC_BF16X3 && prec != CORR_PREC_BF16) return CORR_ERR_INVALID_ARG;
             if (r != 4) return CORR_ERR_UNSUPPORTED;
             if (!(pyr->reps & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
+            hipEvent_t* ev = nullptr;
+            if (pyr->prof_on && pyr->prof_ev && pyr->prof_n < CORR_PROF_LOOKUPS)
+                ev = pyr->prof_ev + (size_t)pyr->prof_n * (L + 2);
+            if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CORR_ERR_HIP;
             e = launch_binning(pyr, coords, r, out, s);
-            if (e == hipSuccess) e = launch_block(pyr, coords, r, (int)prec, out, s);
+            if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
+            if (e == hipSuccess) e = launch_block(pyr, coords, r, (int)prec, out, s, ev ? ev + 2 : nullptr);
+            if (ev && e == hipSuccess) pyr->prof_n++;
             break;
         }
         case CORR_MODE_ONDEMAND: {
@@ -275,12 +283,57 @@ corr_status corr_sample(const float* fmap1, corr_pyramid* pyr, const float* coor
 corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, void* stream) {
     if (!pyr || !stats) return CORR_ERR_INVALID_ARG;
     if (!(pyr->reps & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
-    long long h[8];
+    long long h[CORR_NSTATS];
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (hipMemcpyAsync(h, pyr->stats, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return CORR_ERR_HIP;
     stats->items = h[0]; stats->query_levels = h[1]; stats->null_query_levels = h[2];
     stats->mma_point_queries = h[3]; stats->used_point_queries = h[4];
+    for (int l = 0; l < 4; ++l) {
+        stats->level_items[l] = h[8 + 4 * l + 0];
+        stats->level_mma_point_queries[l] = h[8 + 4 * l + 1];
+        stats->level_used_point_queries[l] = h[8 + 4 * l + 2];
+        stats->level_queries[l] = h[8 + 4 * l + 3];
+    }
+    return CORR_OK;
+}
+
+corr_status corr_profile_enable(corr_pyramid* pyr, int enable) {
+    if (!pyr) return CORR_ERR_INVALID_ARG;
+    if (enable && !pyr->prof_ev) {
+        const int n = CORR_PROF_LOOKUPS * (pyr->L + 2);
+        pyr->prof_ev = new (std::nothrow) hipEvent_t[n];
+        if (!pyr->prof_ev) return CORR_ERR_OOM;
+        for (int i = 0; i < n; ++i)
+            if (hipEventCreate(&pyr->prof_ev[i]) != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(pyr->prof_ev[j]);
+                delete[] pyr->prof_ev; pyr->prof_ev = nullptr;
+                return CORR_ERR_HIP;
+            }
+    }
+    pyr->prof_on = enable ? 1 : 0;
+    pyr->prof_n = 0;
+    return CORR_OK;
+}
+
+corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof) {
+    if (!pyr || !prof) return CORR_ERR_INVALID_ARG;
+    memset(prof, 0, sizeof(*prof));
+    if (!pyr->prof_ev) return CORR_OK;
+    const int per = pyr->L + 2;
+    for (int i = 0; i < pyr->prof_n; ++i) {
+        hipEvent_t* ev = pyr->prof_ev + (size_t)i * per;
+        if (hipEventSynchronize(ev[per - 1]) != hipSuccess) return CORR_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev[0], ev[1]) != hipSuccess) return CORR_ERR_HIP;
+        prof->binning_ms += ms;
+        for (int l = 0; l < pyr->L; ++l) {
+            if (hipEventElapsedTime(&ms, ev[1 + l], ev[2 + l]) != hipSuccess) return CORR_ERR_HIP;
+            prof->block_ms[l] += ms;
+        }
+    }
+    prof->lookups = pyr->prof_n;
+    pyr->prof_n = 0;
     return CORR_OK;
 }
 

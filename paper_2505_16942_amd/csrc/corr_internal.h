@@ -10,6 +10,8 @@
 #define CORR_PAD 16            // window origin of cell 0 along an axis is -CORR_PAD
 #define CORR_GROUP 64          // queries per work item
 #define CORR_COORD_LIMIT 1048576.0f
+#define CORR_NSTATS 24
+#define CORR_PROF_LOOKUPS 256
 
 // Geometry of one level: size, target-cell side (1 << shift), cell grid.
 struct LevelGeom {
@@ -39,11 +41,14 @@ struct corr_pyramid {
     int* perm;                     // [L*B*H*W] queries sorted by cell
     int4* items;                   // [max_items] {cell id, first perm index, n queries, level}
     int* level_item_off;           // [L+1] first item of each level, last = total
-    long long* stats;              // [8]
+    long long* stats;              // [CORR_NSTATS]: 0..4 totals, 8+4*l+{0,1,2,3} per level
     // CORR_MODE_FULLVOLUME cache
     float* vol[CORR_MAX_L];        // [B][H*W][H_l*W_l]
     int vol_valid;
     size_t bytes;
+    // timing hook
+    int prof_on, prof_n;
+    hipEvent_t* prof_ev;           // [CORR_PROF_LOOKUPS][L + 2]
 };
 
 static inline int corr_level_dim(int v, int l) { return v >> l; }
@@ -52,7 +57,8 @@ static inline int corr_level_dim(int v, int l) { return v >> l; }
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
                                  uint16_t* const* split, float* const* nhwc, hipStream_t s);
 hipError_t launch_binning(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
-hipError_t launch_block(corr_pyramid* p, const float* coords, int r, int prec, float* out, hipStream_t s);
+hipError_t launch_block(corr_pyramid* p, const float* coords, int r, int prec, float* out, hipStream_t s,
+                        hipEvent_t* level_done);
 hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
 hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s);
 hipError_t launch_fullvol_sample(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);

@@ -103,17 +103,18 @@ def _warp(f1: np.ndarray, flow: np.ndarray) -> np.ndarray:
     y0 = np.floor(py).astype(np.int64)
     ax = (px - x0).astype(np.float32)
     ay = (py - y0).astype(np.float32)
-    out = np.zeros((D, H, W), dtype=np.float32)
-    flat = f1.reshape(D, H * W)
+    # gather whole feature vectors (rows of a channels-last copy)
+    rows = np.ascontiguousarray(f1.reshape(D, H * W).T)
+    acc = np.zeros((H * W, D), dtype=np.float32)
     for dy in (0, 1):
         for dx in (0, 1):
             xi = x0 + dx
             yi = y0 + dy
             ok = (xi >= 0) & (xi < W) & (yi >= 0) & (yi < H)
-            wgt = (ax if dx else 1.0 - ax) * (ay if dy else 1.0 - ay) * ok
+            wgt = ((ax if dx else 1.0 - ax) * (ay if dy else 1.0 - ay) * ok).astype(np.float32)
             idx = (np.clip(yi, 0, H - 1) * W + np.clip(xi, 0, W - 1)).reshape(-1)
-            out += flat[:, idx].reshape(D, H, W) * wgt[None].astype(np.float32)
-    return out
+            acc += rows[idx] * wgt.reshape(-1, 1)
+    return np.ascontiguousarray(acc.T).reshape(D, H, W)
 
 
 def features(cfg: dict) -> tuple[np.ndarray, np.ndarray]:
