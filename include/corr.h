@@ -116,9 +116,10 @@ size_t corr_workspace_bytes(unsigned reps, int B, int H, int W, int D, int L);
 /*
  * Counters of the last CORR_MODE_BLOCK call on this pyramid (written by the binning pass).
  * Synchronises `stream` and copies them to the host.
- *   items            work items = (target cell window, group of <= 64 queries) pairs
+ *   items            work items = (target cell, group of <= 64 of its queries) pairs
  *   query_levels     B*H*W*L
- *   null_query_levels  query-levels whose whole window lies outside the level (written as zeros)
+ *   null_query_levels  query-levels whose cell window lies wholly outside the level (written as zeros,
+ *                      no contraction)
  *   mma_point_queries  sum over items of window points x queries padded to 16: the contraction
  *                      work actually issued is 2*D*mma_point_queries flop per bf16 term
  *   used_point_queries sum over items of window points x real queries
@@ -139,22 +140,25 @@ corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, vo
 
 /*
  * Timing hook for benchmarks.  While enabled, every CORR_MODE_BLOCK call records HIP events on its
- * stream before the binning pass, after it, and after each level's contraction kernel (up to 256
+ * stream before the binning pass, after it, and after the block kernel (up to 256
  * lookups between two reads; later ones are not recorded).  corr_profile_read waits for the recorded
  * events, returns the sums of elapsed milliseconds and the number of lookups they cover, and resets.
  */
 typedef struct {
     int64_t lookups;
     double binning_ms;
-    double block_ms[4];      /* contraction + epilogue kernel of level l */
+    double block_ms;         /* contraction + epilogue kernel (all levels) */
 } corr_profile;
 corr_status corr_profile_enable(corr_pyramid* pyr, int enable);
 corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof);
 
-/* Host-side test hook of the binning rule (no device work): for level l and radius r, the
- * side b of a target cell, the window side b + 2r + 1 and the number of cells per axis. */
-corr_status corr_bin_geometry(int H, int W, int l, int r, int* cell, int* window,
-                              int* cells_x, int* cells_y);
+/* Host-side test hook of the binning rule (no device work).  Queries are grouped by the cell
+ * (floor(x) >> 3, floor(y) >> 3) of their level-0 target; for level l < L this returns the side of a
+ * cell in level-l pixels (max(8 >> l, 1)), the window of target pixels a cell owns at that level
+ * (cell + 2*4 + 1 per axis) and the number of cells per axis of the grid (it extends past the image
+ * as far as the coarsest level is in range). */
+corr_status corr_bin_geometry(int H, int W, int L, int l, int* cell_x, int* cell_y,
+                              int* window_x, int* window_y, int* cells_x, int* cells_y);
 
 const char* corr_status_string(corr_status s);
 

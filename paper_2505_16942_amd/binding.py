@@ -43,7 +43,7 @@ class BlockStats(ctypes.Structure):
 
 
 class Profile(ctypes.Structure):
-    _fields_ = [("lookups", ctypes.c_int64), ("binning_ms", ctypes.c_double), ("block_ms", ctypes.c_double * 4)]
+    _fields_ = [("lookups", ctypes.c_int64), ("binning_ms", ctypes.c_double), ("block_ms", ctypes.c_double)]
 
 
 _lib = None
@@ -80,7 +80,7 @@ def load_library():
     lib.corr_profile_enable.restype = ci
     lib.corr_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
     lib.corr_profile_read.restype = ci
-    lib.corr_bin_geometry.argtypes = [ci, ci, ci, ci] + [ctypes.POINTER(ci)] * 4
+    lib.corr_bin_geometry.argtypes = [ci, ci, ci, ci] + [ctypes.POINTER(ci)] * 6
     lib.corr_bin_geometry.restype = ci
     lib.corr_status_string.argtypes = [ci]
     lib.corr_status_string.restype = ctypes.c_char_p
@@ -100,12 +100,12 @@ def corr_workspace_bytes(reps: int, B: int, H: int, W: int, D: int, L: int) -> i
     return int(load_library().corr_workspace_bytes(reps, B, H, W, D, L))
 
 
-def corr_bin_geometry(H: int, W: int, l: int, r: int):
-    vals = [ctypes.c_int() for _ in range(4)]
-    st = load_library().corr_bin_geometry(H, W, l, r, *[ctypes.byref(v) for v in vals])
+def corr_bin_geometry(H: int, W: int, L: int, l: int):
+    vals = [ctypes.c_int() for _ in range(6)]
+    st = load_library().corr_bin_geometry(H, W, L, l, *[ctypes.byref(v) for v in vals])
     if st != CORR_OK:
         raise CorrError(st, "corr_bin_geometry")
-    return tuple(v.value for v in vals)   # cell, window, cells_x, cells_y
+    return tuple(v.value for v in vals)   # cell_x, cell_y, window_x, window_y, cells_x, cells_y
 
 
 def _dev_f32(t: torch.Tensor, name: str) -> int:
@@ -202,4 +202,4 @@ def corr_profile_read(pyramid: Pyramid) -> dict:
     st = load_library().corr_profile_read(pyramid.handle, ctypes.byref(p))
     if st != CORR_OK:
         raise CorrError(st, "corr_profile_read")
-    return {"lookups": int(p.lookups), "binning_ms": float(p.binning_ms), "block_ms": [float(x) for x in p.block_ms]}
+    return {"lookups": int(p.lookups), "binning_ms": float(p.binning_ms), "block_ms": float(p.block_ms)}

@@ -2,7 +2,8 @@
 // Computation" and "Sparse Volume Sampling"; fused as in "Fused Implementation":
 // the computed block lives only in registers and LDS).
 //
-// One workgroup (4 waves) = one work item = (target cell window, <= 64 queries).
+// One workgroup (4 waves) = one work item = (target cell, <= 64 of its queries),
+// processed for every pyramid level in turn:
 //   contraction : S[pt][q] = <f2_l(window point pt), f1(query q)> over D, in
 //                 32-channel chunks staged through LDS, on
 //                 v_mfma_f32_16x16x32_bf16 with rows = window points and
@@ -12,7 +13,8 @@
 //   epilogue    : S goes to LDS as [pt][query]; each query reads the 2x2 stencil
 //                 of its own (2r+2)^2 sub-window and writes its (2r+1)^2 taps.
 // Window points outside the level are staged as zeros, which is the zero
-// padding of the sampling rule.
+// padding of the sampling rule.  The query features are re-read per level from
+// L2, so HBM sees them once per lookup.
 #include "corr_internal.h"
 
 namespace {
@@ -21,90 +23,80 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int ROWB = 144;   // LDS bytes per staged row: 64 B hi + 64 B lo + 16 B pad (conflict-free b128 reads)
+constexpr int R = CORR_R, K = 2 * R + 1, KK = K * K;
+constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 
 struct BlockArgs {
-    const uint16_t* f1s;        // [B][NC][HW][64]
-    const uint16_t* f2s;        // this level: [B][NC][HlWl][64]
-    const float* coords;        // [B][2][HW]
+    const uint16_t* f1s;                 // [B][NC][HW][64]
+    const uint16_t* f2s[CORR_MAX_L];     // [B][NC][HlWl][64]
+    const float* coords;                 // [B][2][HW]
     const int* perm;
     const int4* items;
-    const int* level_item_off;
+    const int* n_items;
     float* out;
-    int B, HW, W, NC, L, level;
-    LevelGeom g;
+    int B, HW, NC, L;
+    int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
+    CellGrid g;
     float scale;
 };
 
-template <int SHIFT, int R>
+constexpr int cmax(int a, int b) { return a > b ? a : b; }
+
+template <int LVL>
 struct Geo {
-    static constexpr int CELL = 1 << SHIFT;
-    static constexpr int K = 2 * R + 1;
-    static constexpr int WS = CELL + K;            // window side
-    static constexpr int NPTS = WS * WS;
-    static constexpr int NWB = (NPTS + 15) / 16;   // 16-point row blocks
-    static constexpr int WBW = (NWB + 3) / 4;      // row blocks per wave
+    static constexpr int CXL = cmax(CX >> LVL, 1), CYL = cmax(CY >> LVL, 1);
+    static constexpr int WSX = CXL + K, WSY = CYL + K;   // window sides
+    static constexpr int NPTS = WSX * WSY;
+    static constexpr int NWB = (NPTS + 15) / 16;          // 16-point row blocks
+    static constexpr int WBW = (NWB + 3) / 4;             // row blocks per wave
     static constexpr int ROWS = NWB * 16;
     static constexpr int STAGE_BYTES = (ROWS + CORR_GROUP) * ROWB;
     static constexpr int S_BYTES = ROWS * CORR_GROUP * 4;
-    static constexpr int UNION_BYTES = STAGE_BYTES > S_BYTES ? STAGE_BYTES : S_BYTES;
-    static constexpr int META_BYTES = CORR_GROUP * 16;
-    static constexpr int LDS_BYTES = UNION_BYTES + META_BYTES;
+    static constexpr int UNION_BYTES = cmax(STAGE_BYTES, S_BYTES);
     static constexpr int WIN_ITERS = (NPTS * 8 + 255) / 256;
 };
+constexpr int UNION_BYTES = cmax(cmax(Geo<0>::UNION_BYTES, Geo<1>::UNION_BYTES),
+                                 cmax(Geo<2>::UNION_BYTES, Geo<3>::UNION_BYTES));
+constexpr int META_BYTES = CORR_GROUP * 12;
+constexpr int LDS_BYTES = UNION_BYTES + META_BYTES;
 
-template <int SHIFT, int R, bool THREE>
-__global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
-    using G = Geo<SHIFT, R>;
-    extern __shared__ __align__(16) unsigned char smem[];
+struct ItemCtx {
+    int b, u, v, n;          // batch item, absolute cell coordinates, queries in the group
+    int tid, lane, wave;
+    int qoff[2];             // this thread's two 16-byte pieces of the query rows (element offset or -1)
+};
+
+template <int LVL, bool THREE>
+__device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
+                                           const int* q_pix, const float* q_cx, const float* q_cy) {
+    using G = Geo<LVL>;
     unsigned char* win = smem;                               // ROWS x ROWB
     unsigned char* qry = smem + G::ROWS * ROWB;              // 64 x ROWB
     float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging area
-    int* q_pix = reinterpret_cast<int*>(smem + G::UNION_BYTES);
-    int* q_base = q_pix + CORR_GROUP;
-    float* q_fx = reinterpret_cast<float*>(q_base + CORR_GROUP);
-    float* q_fy = q_fx + CORR_GROUP;
+    const int Hl = a.Hl[LVL], Wl = a.Wl[LVL], HWl = Hl * Wl;
+    const int xs = ((c.u << CORR_LOG_CX) >> LVL) - R;        // window origin in level pixels
+    const int ys = ((c.v << CORR_LOG_CY) >> LVL) - R;
+    const int tid = c.tid, lane = c.lane, wave = c.wave;
+    float* o_lvl = a.out + ((size_t)(c.b * a.L + LVL) * KK) * a.HW;
 
-    // XCD-aware item choice: workgroup w runs on XCD w % 8; give each XCD one
-    // contiguous eighth of the level's items (neighbouring cells share window
-    // rows and columns, so they should share an L2).
-    const int first = a.level_item_off[a.level];
-    const int n_items = a.level_item_off[a.level + 1] - first;
-    const int per_xcd = (n_items + 7) >> 3;
-    const int k = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || k >= n_items) return;
-    const int4 item = a.items[first + k];
-    const int cell = item.x - a.g.bin_base;
-    const int n = item.z;
-    const int bx = cell % a.g.nbx;
-    const int by = (cell / a.g.nbx) % a.g.nby;
-    const int b = cell / (a.g.nbx * a.g.nby);
-    const int xs = (bx << SHIFT) - CORR_PAD;                 // window origin in level pixels
-    const int ys = (by << SHIFT) - CORR_PAD;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int HWl = a.g.H * a.g.W;
-
-    // ---- per-query metadata --------------------------------------------------
-    if (tid < CORR_GROUP) {
-        int pix = -1, base = 0;
-        float fx = 0.f, fy = 0.f;
-        if (tid < n) {
-            const int q = a.perm[item.y + tid];
-            pix = q - b * a.HW;
-            const float inv = __uint_as_float((uint32_t)(127 - a.level) << 23);
-            const float cx = a.coords[((size_t)b * 2 + 0) * a.HW + pix] * inv;
-            const float cy = a.coords[((size_t)b * 2 + 1) * a.HW + pix] * inv;
-            const float flx = floorf(cx), fly = floorf(cy);
-            fx = cx - flx; fy = cy - fly;
-            const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;   // in [0, CELL)
-            base = ry * G::WS + rx;
+    // epilogue work split: 18 half-columns (x offset i, y offsets 0..4 or 5..8) dealt round-robin to the waves
+    const bool touches = xs + G::WSX - 1 >= 0 && xs <= Wl - 1 && ys + G::WSY - 1 >= 0 && ys <= Hl - 1;
+    if (!touches) {             // uniform for the workgroup: this level's window is all padding
+        if (lane < c.n) {
+            float* o = o_lvl + q_pix[lane];
+            for (int uidx = wave; uidx < 2 * K; uidx += 4) {
+                const int i = uidx >> 1, j0 = (uidx & 1) ? 5 : 0, j1 = (uidx & 1) ? K : 5;
+                for (int j = j0; j < j1; ++j) o[(size_t)(i * K + j) * a.HW] = 0.f;
+            }
         }
-        q_pix[tid] = pix; q_base[tid] = base; q_fx[tid] = fx; q_fy[tid] = fy;
+        return;
     }
+
     // rows NPTS..ROWS-1 of the window never receive data: keep them zero
     for (int i = tid; i < (G::ROWS - G::NPTS) * (ROWB / 16); i += 256)
         reinterpret_cast<uint4*>(win + G::NPTS * ROWB)[i] = make_uint4(0, 0, 0, 0);
 
-    // ---- staging plan: the same (point, 16-byte piece) per thread for every chunk
+    // staging plan: the same (point, 16-byte piece) per thread for every chunk
     int goff[G::WIN_ITERS];
 #pragma unroll
     for (int it = 0; it < G::WIN_ITERS; ++it) {
@@ -112,18 +104,10 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
         const int pt = idx >> 3, piece = idx & 7;
         goff[it] = -1;
         if (pt < G::NPTS) {
-            const int wy = pt / G::WS, wx = pt - wy * G::WS;
+            const int wy = pt / G::WSX, wx = pt - wy * G::WSX;
             const int y = ys + wy, x = xs + wx;
-            if (y >= 0 && y < a.g.H && x >= 0 && x < a.g.W) goff[it] = (y * a.g.W + x) * 64 + piece * 8;
+            if (y >= 0 && y < Hl && x >= 0 && x < Wl) goff[it] = (y * Wl + x) * 64 + piece * 8;
         }
-    }
-    __syncthreads();
-    int qoff[2];
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int idx = it * 256 + tid;
-        const int pix = q_pix[idx >> 3];
-        qoff[it] = pix < 0 ? -1 : pix * 64 + (idx & 7) * 8;
     }
 
     f32x4 acc[G::WBW][4];
@@ -132,21 +116,21 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int nqf = (n + 15) >> 4;
+    const int nqf = (c.n + 15) >> 4;
     const int frag_off = (lane & 15) * ROWB + (lane >> 4) * 16;
 
     // global -> registers for chunk 0; inside the loop the next chunk's loads are
     // issued right after the LDS stores so that they fly under the MFMAs
     uint4 wv[G::WIN_ITERS], qv[2];
     auto load_chunk = [&](int kc) {
-        const uint16_t* f2c = a.f2s + ((size_t)b * a.NC + kc) * (size_t)HWl * 64;
-        const uint16_t* f1c = a.f1s + ((size_t)b * a.NC + kc) * (size_t)a.HW * 64;
+        const uint16_t* f2c = a.f2s[LVL] + ((size_t)c.b * a.NC + kc) * (size_t)HWl * 64;
+        const uint16_t* f1c = a.f1s + ((size_t)c.b * a.NC + kc) * (size_t)a.HW * 64;
 #pragma unroll
         for (int it = 0; it < G::WIN_ITERS; ++it)
             wv[it] = goff[it] >= 0 ? *reinterpret_cast<const uint4*>(f2c + goff[it]) : make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int it = 0; it < 2; ++it)
-            qv[it] = qoff[it] >= 0 ? *reinterpret_cast<const uint4*>(f1c + qoff[it]) : make_uint4(0, 0, 0, 0);
+            qv[it] = c.qoff[it] >= 0 ? *reinterpret_cast<const uint4*>(f1c + c.qoff[it]) : make_uint4(0, 0, 0, 0);
     };
     load_chunk(0);
 
@@ -194,7 +178,7 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
     }
     __syncthreads();                            // staging area is dead; S may overwrite it
 
-    // ---- S to LDS: lane holds query (lane % 16) of fragment qf, points 4*(lane/16)+v
+    // S to LDS: lane holds query (lane % 16) of fragment qf, points 4*(lane/16)+v
 #pragma unroll
     for (int i = 0; i < G::WBW; ++i) {
         const int wb = wave + 4 * i;
@@ -208,73 +192,99 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
     }
     __syncthreads();
 
-    // ---- bilinear epilogue: lane = query, wave = a quarter of the taps ----------
-    if (lane < n) {
-        const int pix = q_pix[lane], base = q_base[lane];
-        const float fx = q_fx[lane], fy = q_fy[lane];
-        const float w00 = (1.f - fx) * (1.f - fy), w01 = fx * (1.f - fy);
-        const float w10 = (1.f - fx) * fy, w11 = fx * fy;
-        constexpr int KK = G::K * G::K;
-        constexpr int TPW = (KK + 3) / 4;
-        float* o = a.out + ((size_t)(b * a.L + a.level) * KK) * a.HW + pix;
-        const int t0 = wave * TPW, t1 = min(KK, t0 + TPW);
-        for (int t = t0; t < t1; ++t) {
-            const int i = t / G::K, j = t - i * G::K;      // i: x offset, j: y offset
-            const float* s = S + (base + j * G::WS + i) * CORR_GROUP + lane;
-            const float v = w00 * s[0] + w01 * s[CORR_GROUP] + w10 * s[G::WS * CORR_GROUP]
-                          + w11 * s[(G::WS + 1) * CORR_GROUP];
-            o[(size_t)t * a.HW] = v;
+    // bilinear epilogue: lane = query; a wave takes half-columns of taps.  Along a
+    // column the x-interpolated value of each footprint row is reused by two taps.
+    if (lane < c.n) {
+        const float inv = __uint_as_float((uint32_t)(127 - LVL) << 23);   // 2^-LVL
+        const float cxl = q_cx[lane] * inv, cyl = q_cy[lane] * inv;
+        const float flx = floorf(cxl), fly = floorf(cyl);
+        const float fx = cxl - flx, fy = cyl - fly;
+        const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
+        const float* s0 = S + (ry * G::WSX + rx) * CORR_GROUP + lane;
+        float* o = o_lvl + q_pix[lane];
+        for (int uidx = wave; uidx < 2 * K; uidx += 4) {
+            const int i = uidx >> 1, j0 = (uidx & 1) ? 5 : 0, j1 = (uidx & 1) ? K : 5;
+            const float* s = s0 + (j0 * G::WSX + i) * CORR_GROUP;
+            float hprev = s[0] + fx * (s[CORR_GROUP] - s[0]);
+            for (int j = j0; j < j1; ++j) {
+                s += G::WSX * CORR_GROUP;
+                const float hcur = s[0] + fx * (s[CORR_GROUP] - s[0]);
+                o[(size_t)(i * K + j) * a.HW] = hprev + fy * (hcur - hprev);
+                hprev = hcur;
+            }
         }
     }
-}
-
-template <int SHIFT, int R, bool THREE>
-hipError_t launch_level(const BlockArgs& a, int max_items, hipStream_t s) {
-    using G = Geo<SHIFT, R>;
-    static bool attr_set = false;
-    auto kfn = block_kernel<SHIFT, R, THREE>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const int grid = ((max_items + 7) / 8) * 8;
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(256), G::LDS_BYTES, s, a);
-    return hipGetLastError();
+    __syncthreads();                            // S is dead; the next level may stage
 }
 
 template <bool THREE>
-hipError_t launch_all_levels(corr_pyramid* p, const float* coords, float* out, hipStream_t s,
-                             hipEvent_t* level_done) {
-    const int HW = p->H * p->W, BN = p->B * HW;
-    for (int l = 0; l < p->L; ++l) {
-        BlockArgs a;
-        a.f1s = p->f1_split; a.f2s = p->f2_split[l]; a.coords = coords; a.perm = p->perm;
-        a.items = p->items; a.level_item_off = p->level_item_off; a.out = out;
-        a.B = p->B; a.HW = HW; a.W = p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L; a.level = l;
-        a.g = p->lv[l];
-        a.scale = 1.0f / sqrtf((float)p->D);
-        const int cells = p->B * p->lv[l].nbx * p->lv[l].nby;
-        const int max_items = BN / CORR_GROUP + (cells < BN ? cells : BN) + 1;
-        hipError_t e;
-        switch (p->lv[l].shift) {
-            case 3: e = launch_level<3, 4, THREE>(a, max_items, s); break;
-            case 2: e = launch_level<2, 4, THREE>(a, max_items, s); break;
-            case 1: e = launch_level<1, 4, THREE>(a, max_items, s); break;
-            default: e = launch_level<0, 4, THREE>(a, max_items, s); break;
+__global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    int* q_pix = reinterpret_cast<int*>(smem + UNION_BYTES);
+    float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP);
+    float* q_cy = q_cx + CORR_GROUP;
+
+    // XCD-aware item choice: workgroup w runs on XCD w % 8; give each XCD one
+    // contiguous eighth of the items (neighbouring cells share window rows and
+    // columns, so they should share an L2).
+    const int n_items = *a.n_items;
+    const int per_xcd = (n_items + 7) >> 3;
+    const int k = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || k >= n_items) return;
+    const int4 item = a.items[k];
+    ItemCtx c;
+    c.tid = threadIdx.x; c.lane = c.tid & 63; c.wave = c.tid >> 6;
+    c.n = item.z;
+    c.u = item.x % a.g.nbx + a.g.u_min;
+    c.v = (item.x / a.g.nbx) % a.g.nby + a.g.v_min;
+    c.b = item.x / (a.g.nbx * a.g.nby);
+
+    if (c.tid < CORR_GROUP) {
+        int pix = -1;
+        float cx = 0.f, cy = 0.f;
+        if (c.tid < c.n) {
+            pix = a.perm[item.y + c.tid] - c.b * a.HW;
+            cx = a.coords[((size_t)c.b * 2 + 0) * a.HW + pix];
+            cy = a.coords[((size_t)c.b * 2 + 1) * a.HW + pix];
         }
-        if (e == hipSuccess && level_done) e = hipEventRecord(level_done[l], s);
-        if (e != hipSuccess) return e;
+        q_pix[c.tid] = pix; q_cx[c.tid] = cx; q_cy[c.tid] = cy;
     }
-    return hipSuccess;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int idx = it * 256 + c.tid;
+        const int pix = q_pix[idx >> 3];
+        c.qoff[it] = pix < 0 ? -1 : pix * 64 + (idx & 7) * 8;
+    }
+
+    level_pass<0, THREE>(a, c, smem, q_pix, q_cx, q_cy);
+    if (a.L > 1) level_pass<1, THREE>(a, c, smem, q_pix, q_cx, q_cy);
+    if (a.L > 2) level_pass<2, THREE>(a, c, smem, q_pix, q_cx, q_cy);
+    if (a.L > 3) level_pass<3, THREE>(a, c, smem, q_pix, q_cx, q_cy);
+}
+
+template <bool THREE>
+hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStream_t s) {
+    static bool attr_set = false;
+    auto kfn = block_kernel<THREE>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    BlockArgs a;
+    a.f1s = p->f1_split; a.coords = coords; a.perm = p->perm; a.items = p->items; a.n_items = p->n_items;
+    a.out = out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L; a.g = p->grid;
+    for (int l = 0; l < CORR_MAX_L; ++l) { a.f2s[l] = p->f2_split[l]; a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; }
+    a.scale = 1.0f / sqrtf((float)p->D);
+    const int grid = ((p->max_items + 7) / 8) * 8;
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(256), LDS_BYTES, s, a);
+    return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_block(corr_pyramid* p, const float* coords, int r, int prec, float* out, hipStream_t s,
-                        hipEvent_t* level_done) {
-    (void)r;   // built for r = 4; the caller has checked
-    return prec == CORR_PREC_BF16 ? launch_all_levels<false>(p, coords, out, s, level_done)
-                                  : launch_all_levels<true>(p, coords, out, s, level_done);
+hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s) {
+    return prec == CORR_PREC_BF16 ? launch_items<false>(p, coords, out, s) : launch_items<true>(p, coords, out, s);
 }

@@ -20,23 +20,12 @@ corr_status check_dims(int B, int H, int W, int D, int L) {
     return CORR_OK;
 }
 
-void fill_geometry(corr_pyramid* p, int r) {
-    int base = 0, items = 0;
+void fill_geometry(corr_pyramid* p) {
     const int BN = p->B * p->H * p->W;
-    for (int l = 0; l < p->L; ++l) {
-        LevelGeom& g = p->lv[l];
-        g.H = p->H >> l; g.W = p->W >> l;
-        g.shift = 3 - l;
-        g.nbx = ((g.W - 1 + CORR_PAD) >> g.shift) + 1;
-        g.nby = ((g.H - 1 + CORR_PAD) >> g.shift) + 1;
-        g.bin_base = base;
-        const int cells = p->B * g.nbx * g.nby;
-        base += cells;
-        items += BN / CORR_GROUP + (cells < BN ? cells : BN) + 1;
-    }
-    (void)r;
-    p->nbins = base;
-    p->max_items = items;
+    for (int l = 0; l < CORR_MAX_L; ++l) { p->Hl[l] = p->H >> l; p->Wl[l] = p->W >> l; }
+    corr_fill_grid(&p->grid, p->H, p->W, p->L, CORR_R);
+    p->nbins = p->B * p->grid.nbx * p->grid.nby;
+    p->max_items = BN / CORR_GROUP + (p->nbins < BN ? p->nbins : BN) + 1;
 }
 
 template <typename T>
@@ -53,7 +42,7 @@ void free_volume(corr_pyramid* p) {
     for (int l = 0; l < CORR_MAX_L; ++l)
         if (p->vol[l]) {
             (void)hipFree(p->vol[l]);
-            p->bytes -= (size_t)4 * p->B * p->H * p->W * p->lv[l].H * p->lv[l].W;
+            p->bytes -= (size_t)4 * p->B * p->H * p->W * p->Hl[l] * p->Wl[l];
             p->vol[l] = nullptr;
         }
     p->vol_valid = 0;
@@ -65,10 +54,10 @@ void free_all(corr_pyramid* p) {
     for (int l = 0; l < CORR_MAX_L; ++l) { (void)hipFree(p->f2_nhwc[l]); (void)hipFree(p->f2_split[l]); }
     (void)hipFree(p->bin_count); (void)hipFree(p->bin_off); (void)hipFree(p->q_bin); (void)hipFree(p->q_rank);
     if (p->prof_ev) {
-        for (int i = 0; i < CORR_PROF_LOOKUPS * (p->L + 2); ++i) (void)hipEventDestroy(p->prof_ev[i]);
+        for (int i = 0; i < CORR_PROF_LOOKUPS * 3; ++i) (void)hipEventDestroy(p->prof_ev[i]);
         delete[] p->prof_ev;
     }
-    (void)hipFree(p->perm); (void)hipFree(p->items); (void)hipFree(p->level_item_off); (void)hipFree(p->stats);
+    (void)hipFree(p->perm); (void)hipFree(p->items); (void)hipFree(p->n_items); (void)hipFree(p->stats);
     delete p;
 }
 
@@ -86,31 +75,31 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
     if (!p) return CORR_ERR_OOM;
     memset(p, 0, sizeof(*p));
     p->B = B; p->H = H; p->W = W; p->D = D; p->L = L; p->reps = reps;
-    fill_geometry(p, 4);
+    fill_geometry(p);
     const size_t HW = (size_t)H * W, BN = (size_t)B * HW;
     corr_status st = CORR_OK;
     auto need = [&](corr_status s) { if (st == CORR_OK) st = s; };
     if (reps & CORR_REP_F32) {
         need(dev_alloc(&p->f1_nhwc, BN * D, &p->bytes));
         for (int l = 0; l < L; ++l)
-            need(dev_alloc(&p->f2_nhwc[l], (size_t)B * p->lv[l].H * p->lv[l].W * D, &p->bytes));
+            need(dev_alloc(&p->f2_nhwc[l], (size_t)B * p->Hl[l] * p->Wl[l] * D, &p->bytes));
     }
     if (reps & CORR_REP_SPLIT) {
         need(dev_alloc(&p->f1_split, BN * D * 2, &p->bytes));
         for (int l = 0; l < L; ++l)
-            need(dev_alloc(&p->f2_split[l], (size_t)B * p->lv[l].H * p->lv[l].W * D * 2, &p->bytes));
+            need(dev_alloc(&p->f2_split[l], (size_t)B * p->Hl[l] * p->Wl[l] * D * 2, &p->bytes));
         need(dev_alloc(&p->bin_count, (size_t)p->nbins, &p->bytes));
         need(dev_alloc(&p->bin_off, (size_t)p->nbins, &p->bytes));
-        need(dev_alloc(&p->q_bin, BN * L, &p->bytes));
-        need(dev_alloc(&p->q_rank, BN * L, &p->bytes));
-        need(dev_alloc(&p->perm, BN * L, &p->bytes));
+        need(dev_alloc(&p->q_bin, BN, &p->bytes));
+        need(dev_alloc(&p->q_rank, BN, &p->bytes));
+        need(dev_alloc(&p->perm, BN, &p->bytes));
         need(dev_alloc(&p->items, (size_t)p->max_items, &p->bytes));
-        need(dev_alloc(&p->level_item_off, (size_t)CORR_MAX_L + 1, &p->bytes));
+        need(dev_alloc(&p->n_items, (size_t)4, &p->bytes));
         need(dev_alloc(&p->stats, (size_t)CORR_NSTATS, &p->bytes));
         if (st == CORR_OK) {
             if (hipMemset(p->bin_count, 0, sizeof(int) * p->nbins) != hipSuccess ||
                 hipMemset(p->stats, 0, sizeof(long long) * CORR_NSTATS) != hipSuccess ||
-                hipMemset(p->level_item_off, 0, sizeof(int) * (CORR_MAX_L + 1)) != hipSuccess)
+                hipMemset(p->n_items, 0, sizeof(int) * 4) != hipSuccess)
                 st = CORR_ERR_HIP;
         }
     }
@@ -155,24 +144,28 @@ size_t corr_workspace_bytes(unsigned reps, int B, int H, int W, int D, int L) {
         corr_pyramid tmp;
         memset(&tmp, 0, sizeof(tmp));
         tmp.B = B; tmp.H = H; tmp.W = W; tmp.D = D; tmp.L = L;
-        fill_geometry(&tmp, 4);
+        fill_geometry(&tmp);
         const size_t BN = (size_t)B * H * W;
-        bytes += (size_t)tmp.nbins * 8 + BN * L * 12 + (size_t)tmp.max_items * 16
-               + (CORR_MAX_L + 1) * 4 + 64;
+        bytes += (size_t)tmp.nbins * 8 + BN * 12 + (size_t)tmp.max_items * 16 + 16 + CORR_NSTATS * 8;
     }
     return bytes;
 }
 
 size_t corr_pyramid_bytes(const corr_pyramid* pyr) { return pyr ? pyr->bytes : 0; }
 
-corr_status corr_bin_geometry(int H, int W, int l, int r, int* cell, int* window, int* cells_x, int* cells_y) {
-    if (H <= 0 || W <= 0 || l < 0 || l >= CORR_MAX_L || r < 1 || r > 4) return CORR_ERR_INVALID_ARG;
-    if ((H >> l) < 1 || (W >> l) < 1) return CORR_ERR_INVALID_ARG;
-    const int shift = 3 - l;
-    if (cell) *cell = 1 << shift;
-    if (window) *window = (1 << shift) + 2 * r + 1;
-    if (cells_x) *cells_x = (((W >> l) - 1 + CORR_PAD) >> shift) + 1;
-    if (cells_y) *cells_y = (((H >> l) - 1 + CORR_PAD) >> shift) + 1;
+corr_status corr_bin_geometry(int H, int W, int L, int l, int* cell_x, int* cell_y, int* window_x, int* window_y,
+                              int* cells_x, int* cells_y) {
+    if (H <= 0 || W <= 0 || !level_sizes_ok(H, W, L) || l < 0 || l >= L) return CORR_ERR_INVALID_ARG;
+    CellGrid g;
+    corr_fill_grid(&g, H, W, L, CORR_R);
+    const int cx = ((1 << g.log_cx) >> l) > 1 ? ((1 << g.log_cx) >> l) : 1;
+    const int cy = ((1 << g.log_cy) >> l) > 1 ? ((1 << g.log_cy) >> l) : 1;
+    if (cell_x) *cell_x = cx;
+    if (cell_y) *cell_y = cy;
+    if (window_x) *window_x = cx + 2 * CORR_R + 1;
+    if (window_y) *window_y = cy + 2 * CORR_R + 1;
+    if (cells_x) *cells_x = g.nbx;
+    if (cells_y) *cells_y = g.nby;
     return CORR_OK;
 }
 
@@ -237,11 +230,12 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec, const float* f
             if (!(pyr->reps & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
             hipEvent_t* ev = nullptr;
             if (pyr->prof_on && pyr->prof_ev && pyr->prof_n < CORR_PROF_LOOKUPS)
-                ev = pyr->prof_ev + (size_t)pyr->prof_n * (L + 2);
+                ev = pyr->prof_ev + (size_t)pyr->prof_n * 3;
             if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CORR_ERR_HIP;
-            e = launch_binning(pyr, coords, r, out, s);
+            e = launch_binning(pyr, coords, out, s);
             if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
-            if (e == hipSuccess) e = launch_block(pyr, coords, r, (int)prec, out, s, ev ? ev + 2 : nullptr);
+            if (e == hipSuccess) e = launch_block(pyr, coords, (int)prec, out, s);
+            if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
             if (ev && e == hipSuccess) pyr->prof_n++;
             break;
         }
@@ -259,7 +253,7 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec, const float* f
                     if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) return CORR_ERR_HIP;
                     if (need + (256u << 20) > free_b) return CORR_ERR_OOM;
                     for (int l = 0; l < L; ++l) {
-                        st = dev_alloc(&pyr->vol[l], (size_t)B * H * W * pyr->lv[l].H * pyr->lv[l].W, &pyr->bytes);
+                        st = dev_alloc(&pyr->vol[l], (size_t)B * H * W * pyr->Hl[l] * pyr->Wl[l], &pyr->bytes);
                         if (st != CORR_OK) { free_volume(pyr); return st; }
                     }
                 }
@@ -301,7 +295,7 @@ corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, vo
 corr_status corr_profile_enable(corr_pyramid* pyr, int enable) {
     if (!pyr) return CORR_ERR_INVALID_ARG;
     if (enable && !pyr->prof_ev) {
-        const int n = CORR_PROF_LOOKUPS * (pyr->L + 2);
+        const int n = CORR_PROF_LOOKUPS * 3;
         pyr->prof_ev = new (std::nothrow) hipEvent_t[n];
         if (!pyr->prof_ev) return CORR_ERR_OOM;
         for (int i = 0; i < n; ++i)
@@ -320,17 +314,14 @@ corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof) {
     if (!pyr || !prof) return CORR_ERR_INVALID_ARG;
     memset(prof, 0, sizeof(*prof));
     if (!pyr->prof_ev) return CORR_OK;
-    const int per = pyr->L + 2;
     for (int i = 0; i < pyr->prof_n; ++i) {
-        hipEvent_t* ev = pyr->prof_ev + (size_t)i * per;
-        if (hipEventSynchronize(ev[per - 1]) != hipSuccess) return CORR_ERR_HIP;
+        hipEvent_t* ev = pyr->prof_ev + (size_t)i * 3;
+        if (hipEventSynchronize(ev[2]) != hipSuccess) return CORR_ERR_HIP;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ev[0], ev[1]) != hipSuccess) return CORR_ERR_HIP;
         prof->binning_ms += ms;
-        for (int l = 0; l < pyr->L; ++l) {
-            if (hipEventElapsedTime(&ms, ev[1 + l], ev[2 + l]) != hipSuccess) return CORR_ERR_HIP;
-            prof->block_ms[l] += ms;
-        }
+        if (hipEventElapsedTime(&ms, ev[1], ev[2]) != hipSuccess) return CORR_ERR_HIP;
+        prof->block_ms += ms;
     }
     prof->lookups = pyr->prof_n;
     pyr->prof_n = 0;

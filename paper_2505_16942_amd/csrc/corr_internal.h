@@ -7,25 +7,32 @@
 
 #define CORR_MAX_L 4
 #define CORR_CHUNK 32          // channels per chunk plane of the split representation
-#define CORR_PAD 16            // window origin of cell 0 along an axis is -CORR_PAD
 #define CORR_GROUP 64          // queries per work item
+#define CORR_R 4               // radius the block kernels are built for
+#define CORR_LOG_CX 3          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
+#define CORR_LOG_CY 3
 #define CORR_COORD_LIMIT 1048576.0f
 #define CORR_NSTATS 24
 #define CORR_PROF_LOOKUPS 256
 
-// Geometry of one level: size, target-cell side (1 << shift), cell grid.
-struct LevelGeom {
-    int H, W;          // level size
-    int shift;         // cell side b = 1 << shift
-    int nbx, nby;      // cells per axis
-    int bin_base;      // first global cell id of this level
+// Target-cell grid.  A query belongs to the cell (floor(cx) >> LOG_CX,
+// floor(cy) >> LOG_CY).  Because floor(c / 2^l) == floor(c) >> l, all queries of
+// a cell have, at every level l, footprint origins inside one aligned run of
+// max(CX >> l, 1) x max(CY >> l, 1) level-l pixels, so one fixed window per
+// level serves the whole cell.
+struct CellGrid {
+    int log_cx, log_cy;
+    int u_min, v_min;      // cell coordinates of grid entry (0, 0); may be negative
+    int nbx, nby;          // cells per axis (covers every query that is in range at some level)
+    int r;
 };
 
 struct corr_pyramid {
     int B, H, W, D, L;
     unsigned reps;
-    LevelGeom lv[CORR_MAX_L];
-    int nbins;                     // all levels, all batch items
+    int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
+    CellGrid grid;
+    int nbins;                     // B * nbx * nby
     int max_items;
     // CORR_REP_F32: channels-last fp32
     float* f1_nhwc;                // [B][H*W][D]
@@ -36,11 +43,11 @@ struct corr_pyramid {
     // block-mode workspace
     int* bin_count;                // [nbins] zero between calls
     int* bin_off;                  // [nbins] exclusive prefix of counts
-    int* q_bin;                    // [L][B*H*W] cell id or -1
-    int* q_rank;                   // [L][B*H*W] slot within the cell
-    int* perm;                     // [L*B*H*W] queries sorted by cell
-    int4* items;                   // [max_items] {cell id, first perm index, n queries, level}
-    int* level_item_off;           // [L+1] first item of each level, last = total
+    int* q_bin;                    // [B*H*W] cell id or -1
+    int* q_rank;                   // [B*H*W] slot within the cell
+    int* perm;                     // [B*H*W] queries sorted by cell
+    int4* items;                   // [max_items] {cell id, first perm index, n queries, 0}
+    int* n_items;                  // [1]
     long long* stats;              // [CORR_NSTATS]: 0..4 totals, 8+4*l+{0,1,2,3} per level
     // CORR_MODE_FULLVOLUME cache
     float* vol[CORR_MAX_L];        // [B][H*W][H_l*W_l]
@@ -48,17 +55,27 @@ struct corr_pyramid {
     size_t bytes;
     // timing hook
     int prof_on, prof_n;
-    hipEvent_t* prof_ev;           // [CORR_PROF_LOOKUPS][L + 2]
+    hipEvent_t* prof_ev;           // [CORR_PROF_LOOKUPS][3]
 };
 
-static inline int corr_level_dim(int v, int l) { return v >> l; }
+// Fills `g` for level sizes (H >> l, W >> l), l < L, and radius r.
+static inline void corr_fill_grid(CellGrid* g, int H, int W, int L, int r) {
+    g->log_cx = CORR_LOG_CX; g->log_cy = CORR_LOG_CY; g->r = r;
+    const int m = L - 1;                       // the coarsest level reaches furthest outside
+    // in range at level m  <=>  floor(c) >> m in [-r-1, W_m + r - 1]
+    const int lo_x = (-r - 1) * (1 << m), hi_x = ((W >> m) + r) * (1 << m) - 1;
+    const int lo_y = (-r - 1) * (1 << m), hi_y = ((H >> m) + r) * (1 << m) - 1;
+    g->u_min = lo_x >> g->log_cx;              // arithmetic shift = floor
+    g->v_min = lo_y >> g->log_cy;
+    g->nbx = (hi_x >> g->log_cx) - g->u_min + 1;
+    g->nby = (hi_y >> g->log_cy) - g->v_min + 1;
+}
 
 // launchers (each enqueues on `s` and returns hipGetLastError())
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
                                  uint16_t* const* split, float* const* nhwc, hipStream_t s);
-hipError_t launch_binning(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
-hipError_t launch_block(corr_pyramid* p, const float* coords, int r, int prec, float* out, hipStream_t s,
-                        hipEvent_t* level_done);
+hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipStream_t s);
+hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
 hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
 hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s);
 hipError_t launch_fullvol_sample(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);

@@ -105,9 +105,9 @@ hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s) {
     if (e != hipSuccess) return e;
     for (int l = 1; l < p->L; ++l) {
         const size_t rows = (size_t)p->B * N;
-        const size_t total = rows * p->lv[l].H * p->lv[l].W;
+        const size_t total = rows * p->Hl[l] * p->Wl[l];
         hipLaunchKernelGGL(vol_pool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           p->vol[l - 1], p->vol[l], rows, p->lv[l - 1].H, p->lv[l - 1].W, p->lv[l].H, p->lv[l].W);
+                           p->vol[l - 1], p->vol[l], rows, p->Hl[l - 1], p->Wl[l - 1], p->Hl[l], p->Wl[l]);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -118,7 +118,7 @@ hipError_t launch_fullvol_sample(corr_pyramid* p, const float* coords, int r, fl
     FvArgs a;
     for (int l = 0; l < CORR_MAX_L; ++l) {
         a.vol[l] = l < p->L ? p->vol[l] : nullptr;
-        a.Hl[l] = p->lv[l].H; a.Wl[l] = p->lv[l].W;
+        a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
     }
     a.coords = coords; a.out = out; a.B = p->B; a.HW = p->H * p->W; a.L = p->L; a.r = r;
     const int K = 2 * r + 1;

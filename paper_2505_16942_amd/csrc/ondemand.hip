@@ -102,7 +102,7 @@ hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* o
     a.B = p->B; a.HW = p->H * p->W; a.D = p->D; a.L = p->L; a.r = r;
     for (int l = 0; l < CORR_MAX_L; ++l) {
         a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr;
-        a.Hl[l] = p->lv[l].H; a.Wl[l] = p->lv[l].W;
+        a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
     }
     a.scale = 1.0f / sqrtf((float)p->D);
     const int BN = p->B * p->H * p->W;
