@@ -15,6 +15,7 @@ SOURCES = ["corr_api.hip", "features.hip", "binning.hip", "block.hip", "ondemand
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + INCLUDE, "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
+FLAGS += os.environ.get("CORR_EXTRA_HIPCC_FLAGS", "").split()   # for experiments only
 
 
 def _compile(src: str) -> str:

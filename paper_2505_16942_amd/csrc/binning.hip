@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void bin_count_kernel(BinArgs a) {
     if (finite_ok) {
         const int u = ((int)floorf(cx) >> a.g.log_cx) - a.g.u_min;
         const int v = ((int)floorf(cy) >> a.g.log_cy) - a.g.v_min;
-        if (u >= 0 && u < a.g.nbx && v >= 0 && v < a.g.nby) bin = (b * a.g.nby + v) * a.g.nbx + u;
+        if (u >= 0 && u < a.g.nbx && v >= 0 && v < a.g.nby) bin = corr_cell_id(a.g, b, u, v);
     }
     // Neighbouring pixels mostly fall in the same cell: one atomic per run of
     // equal cell ids among consecutive lanes, the rest of the run takes offsets.
@@ -134,8 +134,9 @@ __global__ __launch_bounds__(1024) void bin_scan_kernel(ScanArgs a) {
             a.bin_off[g] = coff;
             a.bin_count[g] = 0;                     // ready for the next lookup
             if (c[k] > 0) {
-                const int u = g % a.g.nbx + a.g.u_min;
-                const int v = (g / a.g.nbx) % a.g.nby + a.g.v_min;
+                int bb, u, v;
+                corr_cell_coords(a.g, g, &bb, &u, &v);
+                u += a.g.u_min; v += a.g.v_min;
                 int items_here = 0, pad_q = 0;
                 for (int s = 0; s < c[k]; s += CORR_GROUP) {
                     const int n = min(CORR_GROUP, c[k] - s);

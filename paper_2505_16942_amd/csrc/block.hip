@@ -5,14 +5,15 @@
 // One workgroup (4 waves) = one work item = (target cell, <= 64 of its queries),
 // processed for every pyramid level in turn:
 //   contraction : S[pt][q] = <f2_l(window point pt), f1(query q)> over D, in
-//                 32-channel chunks staged through LDS, on
-//                 v_mfma_f32_16x16x32_bf16 with rows = window points and
-//                 columns = queries; fp32 features enter as bf16 hi + lo and
+//                 32-channel chunks on v_mfma_f32_16x16x32_bf16 with rows =
+//                 window points (fragments read straight from global memory, each
+//                 by the one wave that owns the row block) and columns = queries
+//                 (staged through LDS, shared by the four waves); fp32 features enter as bf16 hi + lo and
 //                 the three significant partial products are accumulated in
 //                 fp32 (hi*hi + hi*lo + lo*hi), or hi*hi alone in bf16 mode.
 //   epilogue    : S goes to LDS as [pt][query]; each query reads the 2x2 stencil
 //                 of its own (2r+2)^2 sub-window and writes its (2r+1)^2 taps.
-// Window points outside the level are staged as zeros, which is the zero
+// Window points outside the level enter as zero fragments, which is the zero
 // padding of the sampling rule.  The query features are re-read per level from
 // L2, so HBM sees them once per lookup.
 #include "corr_internal.h"
@@ -27,15 +28,16 @@ constexpr int R = CORR_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 
 struct BlockArgs {
-    const uint16_t* f1s;                 // [B][NC][HW][64]
-    const uint16_t* f2s[CORR_MAX_L];     // [B][NC][HlWl][64]
+    const uint16_t* f1s;                 // [NC][B*HW][64]
+    const uint16_t* f2s;                 // [NC][P][64], P = pixels of all levels; level l starts at pix_base[l]
     const float* coords;                 // [B][2][HW]
     const int* perm;
     const int4* items;
     const int* n_items;
     float* out;
     int B, HW, NC, L;
-    int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
+    int Hl[CORR_MAX_L], Wl[CORR_MAX_L], pix_base[CORR_MAX_L];
+    int f1_stride, f2_stride;            // elements between chunk planes
     CellGrid g;
     float scale;
 };
@@ -50,10 +52,9 @@ struct Geo {
     static constexpr int NWB = (NPTS + 15) / 16;          // 16-point row blocks
     static constexpr int WBW = (NWB + 3) / 4;             // row blocks per wave
     static constexpr int ROWS = NWB * 16;
-    static constexpr int STAGE_BYTES = (ROWS + CORR_GROUP) * ROWB;
+    static constexpr int STAGE_BYTES = CORR_GROUP * ROWB;
     static constexpr int S_BYTES = ROWS * CORR_GROUP * 4;
     static constexpr int UNION_BYTES = cmax(STAGE_BYTES, S_BYTES);
-    static constexpr int WIN_ITERS = (NPTS * 8 + 255) / 256;
 };
 constexpr int UNION_BYTES = cmax(cmax(Geo<0>::UNION_BYTES, Geo<1>::UNION_BYTES),
                                  cmax(Geo<2>::UNION_BYTES, Geo<3>::UNION_BYTES));
@@ -63,17 +64,16 @@ constexpr int LDS_BYTES = UNION_BYTES + META_BYTES;
 struct ItemCtx {
     int b, u, v, n;          // batch item, absolute cell coordinates, queries in the group
     int tid, lane, wave;
-    int qoff[2];             // this thread's two 16-byte pieces of the query rows (element offset or -1)
+    int qoff[2];             // element offset (chunk 0) of the two query pieces this thread stages, or -1
 };
 
 template <int LVL, bool THREE>
 __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
                                            const int* q_pix, const float* q_cx, const float* q_cy) {
     using G = Geo<LVL>;
-    unsigned char* win = smem;                               // ROWS x ROWB
-    unsigned char* qry = smem + G::ROWS * ROWB;              // 64 x ROWB
+    unsigned char* qry = smem;                               // 64 x ROWB, this chunk's query rows
     float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging area
-    const int Hl = a.Hl[LVL], Wl = a.Wl[LVL], HWl = Hl * Wl;
+    const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
     const int xs = ((c.u << CORR_LOG_CX) >> LVL) - R;        // window origin in level pixels
     const int ys = ((c.v << CORR_LOG_CY) >> LVL) - R;
     const int tid = c.tid, lane = c.lane, wave = c.wave;
@@ -92,21 +92,21 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         return;
     }
 
-    // rows NPTS..ROWS-1 of the window never receive data: keep them zero
-    for (int i = tid; i < (G::ROWS - G::NPTS) * (ROWB / 16); i += 256)
-        reinterpret_cast<uint4*>(win + G::NPTS * ROWB)[i] = make_uint4(0, 0, 0, 0);
-
-    // staging plan: the same (point, 16-byte piece) per thread for every chunk
-    int goff[G::WIN_ITERS];
+    // Window operand: read from global memory straight into MFMA fragments.  Lane (p, g) =
+    // (lane % 16, lane / 16) holds window point wb*16 + p, channels 8g..8g+7 of the chunk: 16 bytes
+    // of that pixel's 128-byte chunk record (64 B hi, 64 B lo).  A record is read by this wave only,
+    // hi then lo, so every line comes from L2 once.
+    const int p16 = lane & 15, g4 = lane >> 4;
+    int woff[G::WBW];           // element offset of this lane's piece at chunk 0, or -1 (padding)
 #pragma unroll
-    for (int it = 0; it < G::WIN_ITERS; ++it) {
-        const int idx = it * 256 + tid;
-        const int pt = idx >> 3, piece = idx & 7;
-        goff[it] = -1;
+    for (int i = 0; i < G::WBW; ++i) {
+        const int pt = (wave + 4 * i) * 16 + p16;
+        woff[i] = -1;
         if (pt < G::NPTS) {
             const int wy = pt / G::WSX, wx = pt - wy * G::WSX;
             const int y = ys + wy, x = xs + wx;
-            if (y >= 0 && y < Hl && x >= 0 && x < Wl) goff[it] = (y * Wl + x) * 64 + piece * 8;
+            if (y >= 0 && y < Hl && x >= 0 && x < Wl)
+                woff[i] = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * 64 + g4 * 8;
         }
     }
 
@@ -117,17 +117,19 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int nqf = (c.n + 15) >> 4;
-    const int frag_off = (lane & 15) * ROWB + (lane >> 4) * 16;
+    const int frag_off = p16 * ROWB + g4 * 16;
 
-    // global -> registers for chunk 0; inside the loop the next chunk's loads are
-    // issued right after the LDS stores so that they fly under the MFMAs
-    uint4 wv[G::WIN_ITERS], qv[2];
+    uint4 wh[G::WBW], wl[G::WBW], qv[2];
     auto load_chunk = [&](int kc) {
-        const uint16_t* f2c = a.f2s[LVL] + ((size_t)c.b * a.NC + kc) * (size_t)HWl * 64;
-        const uint16_t* f1c = a.f1s + ((size_t)c.b * a.NC + kc) * (size_t)a.HW * 64;
+        const uint16_t* src = a.f2s + (size_t)kc * a.f2_stride;
 #pragma unroll
-        for (int it = 0; it < G::WIN_ITERS; ++it)
-            wv[it] = goff[it] >= 0 ? *reinterpret_cast<const uint4*>(f2c + goff[it]) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < G::WBW; ++i) {
+            wh[i] = woff[i] >= 0 ? *reinterpret_cast<const uint4*>(src + woff[i]) : make_uint4(0, 0, 0, 0);
+            if (THREE)
+                wl[i] = woff[i] >= 0 ? *reinterpret_cast<const uint4*>(src + woff[i] + 32) : make_uint4(0, 0, 0, 0);
+        }
+        // query rows: thread = (query, 16-byte piece of its chunk record)
+        const uint16_t* f1c = a.f1s + (size_t)kc * a.f1_stride;
 #pragma unroll
         for (int it = 0; it < 2; ++it)
             qv[it] = c.qoff[it] >= 0 ? *reinterpret_cast<const uint4*>(f1c + c.qoff[it]) : make_uint4(0, 0, 0, 0);
@@ -135,20 +137,20 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     load_chunk(0);
 
     for (int kc = 0; kc < a.NC; ++kc) {
-        if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk
-#pragma unroll
-        for (int it = 0; it < G::WIN_ITERS; ++it) {
-            const int idx = it * 256 + tid;
-            if ((idx >> 3) < G::NPTS)
-                *reinterpret_cast<uint4*>(win + (idx >> 3) * ROWB + (idx & 7) * 16) = wv[it];
-        }
+        if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk's query rows
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int idx = it * 256 + tid;
             *reinterpret_cast<uint4*>(qry + (idx >> 3) * ROWB + (idx & 7) * 16) = qv[it];
         }
         __syncthreads();
-        if (kc + 1 < a.NC) load_chunk(kc + 1);
+        bf16x8 ch[G::WBW], cl[G::WBW];          // this chunk's window fragments
+#pragma unroll
+        for (int i = 0; i < G::WBW; ++i) {
+            ch[i] = __builtin_bit_cast(bf16x8, wh[i]);
+            if (THREE) cl[i] = __builtin_bit_cast(bf16x8, wl[i]);
+        }
+        if (kc + 1 < a.NC) load_chunk(kc + 1);  // next chunk flies under this chunk's MFMAs
 
         bf16x8 qh[4], ql[4];
 #pragma unroll
@@ -158,19 +160,15 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         }
 #pragma unroll
         for (int i = 0; i < G::WBW; ++i) {
-            const int wb = wave + 4 * i;
-            if (wb < G::NWB) {
-                const bf16x8 wh = *reinterpret_cast<const bf16x8*>(win + wb * 16 * ROWB + frag_off);
-                bf16x8 wl;
-                if (THREE) wl = *reinterpret_cast<const bf16x8*>(win + wb * 16 * ROWB + frag_off + 64);
+            if (wave + 4 * i < G::NWB) {
 #pragma unroll
                 for (int qf = 0; qf < 4; ++qf) {
                     if (qf < nqf) {
                         if (THREE) {
-                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl, qh[qf], acc[i][qf], 0, 0, 0);
-                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh, ql[qf], acc[i][qf], 0, 0, 0);
+                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cl[i], qh[qf], acc[i][qf], 0, 0, 0);
+                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ch[i], ql[qf], acc[i][qf], 0, 0, 0);
                         }
-                        acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh, qh[qf], acc[i][qf], 0, 0, 0);
+                        acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ch[i], qh[qf], acc[i][qf], 0, 0, 0);
                     }
                 }
             }
@@ -235,9 +233,8 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
     ItemCtx c;
     c.tid = threadIdx.x; c.lane = c.tid & 63; c.wave = c.tid >> 6;
     c.n = item.z;
-    c.u = item.x % a.g.nbx + a.g.u_min;
-    c.v = (item.x / a.g.nbx) % a.g.nby + a.g.v_min;
-    c.b = item.x / (a.g.nbx * a.g.nby);
+    corr_cell_coords(a.g, item.x, &c.b, &c.u, &c.v);
+    c.u += a.g.u_min; c.v += a.g.v_min;
 
     if (c.tid < CORR_GROUP) {
         int pix = -1;
@@ -254,7 +251,7 @@ __global__ __launch_bounds__(256, 2) void block_kernel(BlockArgs a) {
     for (int it = 0; it < 2; ++it) {
         const int idx = it * 256 + c.tid;
         const int pix = q_pix[idx >> 3];
-        c.qoff[it] = pix < 0 ? -1 : pix * 64 + (idx & 7) * 8;
+        c.qoff[it] = pix < 0 ? -1 : (c.b * a.HW + pix) * 64 + (idx & 7) * 8;
     }
 
     level_pass<0, THREE>(a, c, smem, q_pix, q_cx, q_cy);
@@ -274,9 +271,10 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
         attr_set = true;
     }
     BlockArgs a;
-    a.f1s = p->f1_split; a.coords = coords; a.perm = p->perm; a.items = p->items; a.n_items = p->n_items;
+    a.f1s = p->f1_split; a.f2s = p->f2_split; a.coords = coords; a.perm = p->perm; a.items = p->items; a.n_items = p->n_items;
     a.out = out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L; a.g = p->grid;
-    for (int l = 0; l < CORR_MAX_L; ++l) { a.f2s[l] = p->f2_split[l]; a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; }
+    for (int l = 0; l < CORR_MAX_L; ++l) { a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; a.pix_base[l] = p->f2_pix_base[l]; }
+    a.f1_stride = p->B * p->H * p->W * 64; a.f2_stride = p->f2_pix_total * 64;
     a.scale = 1.0f / sqrtf((float)p->D);
     const int grid = ((p->max_items + 7) / 8) * 8;
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(256), LDS_BYTES, s, a);

@@ -17,6 +17,9 @@ corr_status check_dims(int B, int H, int W, int D, int L) {
     if (!level_sizes_ok(H, W, L)) return CORR_ERR_INVALID_ARG;
     if (D % CORR_CHUNK != 0 || D > 1024) return CORR_ERR_UNSUPPORTED;
     if ((long long)B * H * W * 81 * L >= (1LL << 31)) return CORR_ERR_UNSUPPORTED;
+    long long px = 0;
+    for (int l = 0; l < L; ++l) px += (long long)(H >> l) * (W >> l);
+    if ((long long)B * px * D * 2 >= (1LL << 31)) return CORR_ERR_UNSUPPORTED;   // 32-bit element offsets
     return CORR_OK;
 }
 
@@ -24,7 +27,7 @@ void fill_geometry(corr_pyramid* p) {
     const int BN = p->B * p->H * p->W;
     for (int l = 0; l < CORR_MAX_L; ++l) { p->Hl[l] = p->H >> l; p->Wl[l] = p->W >> l; }
     corr_fill_grid(&p->grid, p->H, p->W, p->L, CORR_R);
-    p->nbins = p->B * p->grid.nbx * p->grid.nby;
+    p->nbins = p->B * 64 * p->grid.tnx * p->grid.tny;
     p->max_items = BN / CORR_GROUP + (p->nbins < BN ? p->nbins : BN) + 1;
 }
 
@@ -51,7 +54,8 @@ void free_volume(corr_pyramid* p) {
 void free_all(corr_pyramid* p) {
     free_volume(p);
     (void)hipFree(p->f1_nhwc); (void)hipFree(p->f1_split);
-    for (int l = 0; l < CORR_MAX_L; ++l) { (void)hipFree(p->f2_nhwc[l]); (void)hipFree(p->f2_split[l]); }
+    for (int l = 0; l < CORR_MAX_L; ++l) (void)hipFree(p->f2_nhwc[l]);
+    (void)hipFree(p->f2_split);
     (void)hipFree(p->bin_count); (void)hipFree(p->bin_off); (void)hipFree(p->q_bin); (void)hipFree(p->q_rank);
     if (p->prof_ev) {
         for (int i = 0; i < CORR_PROF_LOOKUPS * 3; ++i) (void)hipEventDestroy(p->prof_ev[i]);
@@ -86,8 +90,10 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
     }
     if (reps & CORR_REP_SPLIT) {
         need(dev_alloc(&p->f1_split, BN * D * 2, &p->bytes));
-        for (int l = 0; l < L; ++l)
-            need(dev_alloc(&p->f2_split[l], (size_t)B * p->Hl[l] * p->Wl[l] * D * 2, &p->bytes));
+        size_t px = 0;
+        for (int l = 0; l < L; ++l) { p->f2_pix_base[l] = (int)px; px += (size_t)B * p->Hl[l] * p->Wl[l]; }
+        p->f2_pix_total = (int)px;
+        need(dev_alloc(&p->f2_split, px * D * 2, &p->bytes));
         need(dev_alloc(&p->bin_count, (size_t)p->nbins, &p->bytes));
         need(dev_alloc(&p->bin_off, (size_t)p->nbins, &p->bytes));
         need(dev_alloc(&p->q_bin, BN, &p->bytes));
@@ -187,9 +193,8 @@ corr_status corr_pyramid_build_reps(const float* fmap1, const float* fmap2, int 
     hipStream_t s = static_cast<hipStream_t>(stream);
     p->vol_valid = 0;     // a cached dense volume belongs to the previous pair
     const bool sp = (reps & CORR_REP_SPLIT) != 0, fp = (reps & CORR_REP_F32) != 0;
-    uint16_t* f1s[1] = {p->f1_split};
     float* f1n[1] = {p->f1_nhwc};
-    hipError_t e = launch_build_features(fmap1, B, D, H, W, 1, sp ? f1s : nullptr, fp ? f1n : nullptr, s);
+    hipError_t e = launch_build_features(fmap1, B, D, H, W, 1, sp ? p->f1_split : nullptr, fp ? f1n : nullptr, s);
     if (e == hipSuccess)
         e = launch_build_features(fmap2, B, D, H, W, L, sp ? p->f2_split : nullptr, fp ? p->f2_nhwc : nullptr, s);
     if (e != hipSuccess) {

@@ -24,22 +24,39 @@ struct CellGrid {
     int log_cx, log_cy;
     int u_min, v_min;      // cell coordinates of grid entry (0, 0); may be negative
     int nbx, nby;          // cells per axis (covers every query that is in range at some level)
+    int tnx, tny;          // 8x8-cell super-tiles per axis (grid padded up)
     int r;
 };
+
+// Cell ids are super-tile major: the 64 cells of an 8x8 super-tile are consecutive, so work items
+// that run at the same time on one XCD cover a compact 2-D patch of the target image and find
+// each other's window rows and columns in that XCD's L2.
+__host__ __device__ static inline int corr_cell_id(const CellGrid& g, int b, int u, int v) {   // u, v grid-relative
+    return (((b * g.tny + (v >> 3)) * g.tnx + (u >> 3)) << 6) + ((v & 7) << 3) + (u & 7);
+}
+__host__ __device__ static inline void corr_cell_coords(const CellGrid& g, int id, int* b, int* u, int* v) {
+    const int tile = id >> 6, in = id & 63;
+    *u = (tile % g.tnx) * 8 + (in & 7);
+    *v = ((tile / g.tnx) % g.tny) * 8 + (in >> 3);
+    *b = tile / (g.tnx * g.tny);
+}
 
 struct corr_pyramid {
     int B, H, W, D, L;
     unsigned reps;
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     CellGrid grid;
-    int nbins;                     // B * nbx * nby
+    int nbins;                     // B * 64 * tnx * tny
     int max_items;
     // CORR_REP_F32: channels-last fp32
     float* f1_nhwc;                // [B][H*W][D]
     float* f2_nhwc[CORR_MAX_L];    // [B][H_l*W_l][D]
-    // CORR_REP_SPLIT: [B][D/32][pixels][64] bf16, 32 hi then 32 lo per pixel and chunk
+    // CORR_REP_SPLIT: [D/32][P][64] bf16 (per 32-channel chunk 32 hi then 32 lo), P = all pixels
+    // (f1: B*H*W; f2: every level, level-major then batch: pix_base[l] + b*H_l*W_l + y*W_l + x)
     uint16_t* f1_split;
-    uint16_t* f2_split[CORR_MAX_L];
+    uint16_t* f2_split;
+    int f2_pix_base[CORR_MAX_L];   // first pixel of level l in a chunk plane
+    int f2_pix_total;              // pixels per chunk plane
     // block-mode workspace
     int* bin_count;                // [nbins] zero between calls
     int* bin_off;                  // [nbins] exclusive prefix of counts
@@ -69,11 +86,13 @@ static inline void corr_fill_grid(CellGrid* g, int H, int W, int L, int r) {
     g->v_min = lo_y >> g->log_cy;
     g->nbx = (hi_x >> g->log_cx) - g->u_min + 1;
     g->nby = (hi_y >> g->log_cy) - g->v_min + 1;
+    g->tnx = (g->nbx + 7) >> 3;
+    g->tny = (g->nby + 7) >> 3;
 }
 
 // launchers (each enqueues on `s` and returns hipGetLastError())
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
-                                 uint16_t* const* split, float* const* nhwc, hipStream_t s);
+                                 uint16_t* split, float* const* nhwc, hipStream_t s);
 hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipStream_t s);
 hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
 hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);

@@ -5,7 +5,9 @@
 // A workgroup owns 32 channels x (8 rows x 32 columns) of level 0.  The tile is
 // read once (128 B runs along x), pooled 2x2 in LDS level after level
 // (0.25f * (a + b + c + d), the order of the definition, in fp32) and written as
-//   split : [B][D/32][pixel][32 x bf16 hi | 32 x bf16 lo]   (128 B per pixel)
+//   split : [D/32][P][32 x bf16 hi | 32 x bf16 lo] with P = every pixel of every level and batch
+//           item (level-major, then batch, then row-major), so a 32-channel chunk of a window row
+//           is one contiguous run and all levels share one chunk stride
 //   nhwc  : [B][pixel][D] fp32
 // A level-l pixel is written iff it lies inside the floor-halved level size, so
 // a trailing odd row or column is dropped exactly as the definition says.
@@ -23,7 +25,8 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
 struct LevelOut {
-    uint16_t* split;   // may be null
+    uint16_t* split;   // may be null; base of the whole split buffer
+    size_t ptotal, pbase;   // pixels per chunk plane, first pixel of this level in a plane
     float* nhwc;       // may be null
     int H, W;
 };
@@ -38,7 +41,6 @@ template <int ROWS, int COLS>
 __device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, int b, int kc, int D,
                                            int y0, int x0) {
     constexpr int PITCH = COLS + 1;
-    const int NC = D / CH;
     // one thread = one pixel x 8 channels (16 B of hi, 16 B of lo, 32 B of fp32)
     for (int w = threadIdx.x; w < ROWS * COLS * 4; w += blockDim.x) {
         const int part = w & 3, pix = w >> 2;
@@ -57,7 +59,7 @@ __device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, i
                 hi[k] = f32_to_bf16_rne(v[k]);
                 lw[k] = f32_to_bf16_rne(v[k] - bf16_bits_to_f32(hi[k]));
             }
-            uint16_t* dst = lo.split + (((size_t)b * NC + kc) * npix + p) * (2 * CH) + part * 8;
+            uint16_t* dst = lo.split + ((size_t)kc * lo.ptotal + lo.pbase + (size_t)b * npix + p) * (2 * CH) + part * 8;
             uint4 h4 = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16),
                                   hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
             uint4 l4 = make_uint4(lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16),
@@ -126,11 +128,16 @@ __global__ __launch_bounds__(256) void build_features_kernel(BuildArgs a) {
 }  // namespace
 
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
-                                 uint16_t* const* split, float* const* nhwc, hipStream_t s) {
+                                 uint16_t* split, float* const* nhwc, hipStream_t s) {
     BuildArgs a;
     a.src = nchw; a.B = B; a.D = D; a.H = H; a.W = W; a.nlev = nlev;
+    size_t ptotal = 0;
+    for (int l = 0; l < nlev; ++l) ptotal += (size_t)B * (H >> l) * (W >> l);
+    size_t pbase = 0;
     for (int l = 0; l < CORR_MAX_L; ++l) {
-        a.lv[l].split = (l < nlev && split) ? split[l] : nullptr;
+        a.lv[l].split = l < nlev ? split : nullptr;
+        a.lv[l].ptotal = ptotal; a.lv[l].pbase = pbase;
+        if (l < nlev) pbase += (size_t)B * (H >> l) * (W >> l);
         a.lv[l].nhwc = (l < nlev && nhwc) ? nhwc[l] : nullptr;
         a.lv[l].H = H >> l; a.lv[l].W = W >> l;
     }
