@@ -32,6 +32,11 @@ def main() -> int:
     ap.add_argument("--prec", default="bf16x3", choices=["bf16x3", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run the library's plain copy kernel on 1 GiB (3 launches) so that a counter run "
+                         "sees a kernel of known HBM traffic")
+    ap.add_argument("--compare-modes", action="store_true",
+                    help="additionally time the on-demand and full-volume reference modes (one lookup each)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -66,6 +71,16 @@ def main() -> int:
     out = torch.empty((B, L * K * K, H, W), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     torch.cuda.reset_peak_memory_stats()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per launch
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            cb.corr_copy_f32(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats()
 
     pyr = cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_SPLIT)
 
@@ -138,6 +153,13 @@ def main() -> int:
         "hbm_achieved_GBs": round(hbm_gbs, 1), "hbm_frac": round(hbm_gbs / PEAK_HBM_GBS, 4),
     }
 
+    # measured HBM traffic of the block kernel, if a counter summary for this workload is committed
+    traffic_file = os.path.join(ROOT, "profiles", "block_kernel_%s_hbm_traffic.txt" % args.config)
+    if terms == 3 and os.path.exists(traffic_file):
+        for line in open(traffic_file):
+            if line.startswith("traffic_bytes_per_launch:"):
+                roofline["traffic"] = float(line.split(":")[1])
+
     peak_bytes = int(torch.cuda.max_memory_allocated()) + pyr.bytes()
     result = {
         "metric": "correlation lookups/s (queries x L x 81 taps)", "value": value, "unit": "lookups/s",
@@ -161,6 +183,29 @@ def main() -> int:
         "input_generation_s": round(gen_s, 1),
     }
 
+    if args.compare_modes:
+        # one lookup in each reference mode on the same inputs (full volume only if it fits)
+        pyr2 = cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_F32)
+        modes = {}
+        for name, mode in (("ondemand", cb.CORR_MODE_ONDEMAND), ("fullvolume", cb.CORR_MODE_FULLVOLUME)):
+            try:
+                cb.corr_sample(t1, pyr2, tcs[0], r=r, out=out, mode=mode)      # full volume: builds the volume
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                cb.corr_sample(t1, pyr2, tcs[0], r=r, out=out, mode=mode)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                modes[name] = {"one_lookup_ms": round(ms, 3), "lookups_per_s": lookups_per_call / (ms * 1e-3),
+                               "library_bytes": pyr2.bytes()}
+            except cb.CorrError as err:
+                modes[name] = {"status": str(err), "needs_bytes": cb.corr_full_volume_bytes(B, H, W, L)}
+        modes["block"] = {"one_lookup_ms": round(lookup_ms, 3), "lookups_per_s": lookups_per_call / (lookup_ms * 1e-3),
+                          "library_bytes": pyr.bytes()}
+        result["modes"] = modes
+        pyr2.destroy()
+
     if not args.no_cpu_baseline:
         from oracle import corr_oracle
         rng = np.random.default_rng(cfg["seed"])
@@ -168,7 +213,7 @@ def main() -> int:
         tq = time.perf_counter()
         corr_oracle.lookup_points(f1, f2, c0, np.zeros(1, np.int64), L=L, r=r)
         prep_s = time.perf_counter() - tq          # the oracle's own per-pair preprocessing
-        nq_cal = 512
+        nq_cal = min(B * N, 20000)
         def sample_idx(nq):
             qs = rng.choice(B * N, size=min(nq, B * N), replace=False)
             b, p = qs // N, qs % N
@@ -177,7 +222,7 @@ def main() -> int:
         idx = sample_idx(nq_cal)
         tq = time.perf_counter()
         corr_oracle.lookup_points(f1, f2, c0, idx, L=L, r=r)
-        cal_s = max(time.perf_counter() - tq - prep_s, 1e-3)
+        cal_s = max(time.perf_counter() - tq - prep_s, 0.05)
         nq = int(min(B * N, max(nq_cal, nq_cal * args.cpu_seconds / cal_s)))
         idx = sample_idx(nq)
         tq = time.perf_counter()

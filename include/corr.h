@@ -160,6 +160,10 @@ corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof);
 corr_status corr_bin_geometry(int H, int W, int L, int l, int* cell_x, int* cell_y,
                               int* window_x, int* window_y, int* cells_x, int* cells_y);
 
+/* Measurement aid: a plain grid-stride copy of n floats (device to device) on `stream`.  Profiling
+ * runs use it as the kernel of known size against which the HBM byte counters are scaled. */
+corr_status corr_copy_f32(float* dst, const float* src, size_t n, void* stream);
+
 const char* corr_status_string(corr_status s);
 
 #ifdef __cplusplus

@@ -24,7 +24,7 @@ EXPORTS = [
     "corr_pyramid_build", "corr_pyramid_build_reps", "corr_pyramid_destroy", "corr_pyramid_bytes",
     "corr_sample", "corr_sample_mode", "corr_full_volume_bytes", "corr_workspace_bytes",
     "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry",
-    "corr_status_string",
+    "corr_copy_f32", "corr_status_string",
 ]
 
 
@@ -82,6 +82,8 @@ def load_library():
     lib.corr_profile_read.restype = ci
     lib.corr_bin_geometry.argtypes = [ci, ci, ci, ci] + [ctypes.POINTER(ci)] * 6
     lib.corr_bin_geometry.restype = ci
+    lib.corr_copy_f32.argtypes = [vp, vp, sz, vp]
+    lib.corr_copy_f32.restype = ci
     lib.corr_status_string.argtypes = [ci]
     lib.corr_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -189,6 +191,16 @@ def corr_last_block_stats(pyramid: Pyramid) -> dict:
         v = getattr(s, k)
         out[k] = int(v) if ty is ctypes.c_int64 else [int(x) for x in v]
     return out
+
+
+def corr_copy_f32(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain device copy through the library's copy kernel (counter calibration)."""
+    pd, ps = _dev_f32(dst, "dst"), _dev_f32(src, "src")
+    if dst.numel() != src.numel():
+        raise ValueError("dst and src must have the same number of elements")
+    st = load_library().corr_copy_f32(pd, ps, src.numel(), _stream())
+    if st != CORR_OK:
+        raise CorrError(st, "corr_copy_f32")
 
 
 def corr_profile_enable(pyramid: Pyramid, enable: bool = True) -> None:

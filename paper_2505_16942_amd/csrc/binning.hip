@@ -82,12 +82,8 @@ struct ScanArgs {
 // writes the item list in cell order.
 __global__ __launch_bounds__(1024) void bin_scan_kernel(ScanArgs a) {
     __shared__ int s_wc[16], s_wi[16];
-    __shared__ unsigned long long s_stats[CORR_NSTATS];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    if (t < CORR_NSTATS) s_stats[t] = 0;
     int carry_c = 0, carry_i = 0;
-    long long nit[CORR_MAX_L] = {}, mma[CORR_MAX_L] = {}, used[CORR_MAX_L] = {}, nq[CORR_MAX_L] = {};
-    const int K = 2 * a.g.r + 1;
     const int ntiles = (a.nbins + 4095) / 4096;
     auto load_tile = [&](int tile) {
         const int g0 = tile * 4096 + t * 4;
@@ -133,53 +129,51 @@ __global__ __launch_bounds__(1024) void bin_scan_kernel(ScanArgs a) {
             if (g >= a.nbins) break;
             a.bin_off[g] = coff;
             a.bin_count[g] = 0;                     // ready for the next lookup
-            if (c[k] > 0) {
-                int bb, u, v;
-                corr_cell_coords(a.g, g, &bb, &u, &v);
-                u += a.g.u_min; v += a.g.v_min;
-                int items_here = 0, pad_q = 0;
-                for (int s = 0; s < c[k]; s += CORR_GROUP) {
-                    const int n = min(CORR_GROUP, c[k] - s);
-                    a.items[ioff++] = make_int4(g, coff + s, n, 0);
-                    ++items_here;
-                    pad_q += (n + 15) & ~15;
-                }
-                for (int l = 0; l < a.L; ++l) {
-                    // window of this cell at level l and whether it touches the level at all
-                    const int wsx = max((1 << a.g.log_cx) >> l, 1) + K, wsy = max((1 << a.g.log_cy) >> l, 1) + K;
-                    const int xs = ((u << a.g.log_cx) >> l) - a.g.r, ys = ((v << a.g.log_cy) >> l) - a.g.r;
-                    if (xs + wsx - 1 >= 0 && xs <= a.Wl[l] - 1 && ys + wsy - 1 >= 0 && ys <= a.Hl[l] - 1) {
-                        nit[l] += items_here;
-                        nq[l] += c[k];
-                        mma[l] += (long long)wsx * wsy * pad_q;
-                        used[l] += (long long)wsx * wsy * c[k];
-                    }
-                }
-            }
+            for (int s = 0; s < c[k]; s += CORR_GROUP)
+                a.items[ioff++] = make_int4(g, coff + s, min(CORR_GROUP, c[k] - s), 0);
             coff += c[k];
         }
     }
-    for (int l = 0; l < a.L; ++l)
-        if (nq[l]) {
-            atomicAdd(&s_stats[8 + 4 * l + 0], (unsigned long long)nit[l]);
-            atomicAdd(&s_stats[8 + 4 * l + 1], (unsigned long long)mma[l]);
-            atomicAdd(&s_stats[8 + 4 * l + 2], (unsigned long long)used[l]);
-            atomicAdd(&s_stats[8 + 4 * l + 3], (unsigned long long)nq[l]);
+    if (t == 0) { a.n_items[0] = carry_i; a.n_items[1] = carry_c; }   // items, binned queries
+}
+
+// On request only: work counters of the last binning, recomputed from the cell offsets.
+__global__ __launch_bounds__(256) void bin_stats_kernel(ScanArgs a) {
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int K = 2 * a.g.r + 1;
+    long long v[CORR_MAX_L][4] = {};
+    if (g < a.nbins) {
+        const int end = g + 1 < a.nbins ? a.bin_off[g + 1] : a.n_items[1];
+        const int c = end - a.bin_off[g];
+        if (c > 0) {
+            int bb, u, w;
+            corr_cell_coords(a.g, g, &bb, &u, &w);
+            u += a.g.u_min; w += a.g.v_min;
+            const int items_here = (c + CORR_GROUP - 1) / CORR_GROUP;
+            const int pad_q = (c / CORR_GROUP) * CORR_GROUP + (((c % CORR_GROUP) + 15) & ~15);
+#pragma unroll
+            for (int l = 0; l < CORR_MAX_L; ++l) {
+                if (l >= a.L) break;
+                // window of this cell at level l and whether it touches the level at all
+                const int wsx = max((1 << a.g.log_cx) >> l, 1) + K, wsy = max((1 << a.g.log_cy) >> l, 1) + K;
+                const int xs = ((u << a.g.log_cx) >> l) - a.g.r, ys = ((w << a.g.log_cy) >> l) - a.g.r;
+                if (xs + wsx - 1 >= 0 && xs <= a.Wl[l] - 1 && ys + wsy - 1 >= 0 && ys <= a.Hl[l] - 1) {
+                    v[l][0] = items_here; v[l][1] = (long long)wsx * wsy * pad_q;
+                    v[l][2] = (long long)wsx * wsy * c; v[l][3] = c;
+                }
+            }
         }
-    __syncthreads();
-    if (t == 0) {
-        *a.n_items = carry_i;
-        long long mma_all = 0, used_all = 0, ql = 0;
-        for (int l = 0; l < CORR_MAX_L; ++l) {
-            mma_all += s_stats[8 + 4 * l + 1]; used_all += s_stats[8 + 4 * l + 2]; ql += s_stats[8 + 4 * l + 3];
-        }
-        a.stats[0] = carry_i;                                   // items
-        a.stats[1] = (long long)a.BN * a.L;                     // query-levels
-        a.stats[2] = (long long)a.BN * a.L - ql;                // query-levels that take no contraction
-        a.stats[3] = mma_all;
-        a.stats[4] = used_all;
     }
-    if (t >= 8 && t < CORR_NSTATS) a.stats[t] = (long long)s_stats[t];
+#pragma unroll
+    for (int l = 0; l < CORR_MAX_L; ++l)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            long long x = v[l][k];
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) x += __shfl_xor(x, d, 64);
+            if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(&a.stats[8 + 4 * l + k]), (unsigned long long)x);
+        }
 }
 
 __global__ __launch_bounds__(256) void bin_scatter_kernel(const int* __restrict__ q_bin,
@@ -194,6 +188,23 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(const int* __restrict_
 
 }  // namespace
 
+static ScanArgs scan_args(corr_pyramid* p) {
+    ScanArgs sc;
+    sc.nbins = p->nbins; sc.L = p->L; sc.BN = p->B * p->H * p->W; sc.g = p->grid;
+    for (int l = 0; l < CORR_MAX_L; ++l) { sc.Hl[l] = p->Hl[l]; sc.Wl[l] = p->Wl[l]; }
+    sc.bin_count = p->bin_count; sc.bin_off = p->bin_off; sc.items = p->items;
+    sc.n_items = p->n_items; sc.stats = p->stats;
+    return sc;
+}
+
+// stats[8 + 4*l + {0,1,2,3}] = items, issued and used point-queries, queries of level l
+hipError_t launch_bin_stats(corr_pyramid* p, hipStream_t s) {
+    hipError_t e = hipMemsetAsync(p->stats, 0, sizeof(long long) * CORR_NSTATS, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(bin_stats_kernel, dim3((p->nbins + 255) / 256), dim3(256), 0, s, scan_args(p));
+    return hipGetLastError();
+}
+
 hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipStream_t s) {
     const int HW = p->H * p->W, BN = p->B * HW;
     BinArgs a;
@@ -203,11 +214,7 @@ hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipS
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    ScanArgs sc;
-    sc.nbins = p->nbins; sc.L = p->L; sc.BN = BN; sc.g = p->grid;
-    for (int l = 0; l < CORR_MAX_L; ++l) { sc.Hl[l] = p->Hl[l]; sc.Wl[l] = p->Wl[l]; }
-    sc.bin_count = p->bin_count; sc.bin_off = p->bin_off; sc.items = p->items;
-    sc.n_items = p->n_items; sc.stats = p->stats;
+    ScanArgs sc = scan_args(p);
     hipLaunchKernelGGL(bin_scan_kernel, dim3(1), dim3(1024), 0, s, sc);
     e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -5,15 +5,14 @@
 // One workgroup (4 waves) = one work item = (target cell, <= 64 of its queries),
 // processed for every pyramid level in turn:
 //   contraction : S[pt][q] = <f2_l(window point pt), f1(query q)> over D, in
-//                 32-channel chunks on v_mfma_f32_16x16x32_bf16 with rows =
-//                 window points (fragments read straight from global memory, each
-//                 by the one wave that owns the row block) and columns = queries
-//                 (staged through LDS, shared by the four waves); fp32 features enter as bf16 hi + lo and
+//                 32-channel chunks staged through LDS, on
+//                 v_mfma_f32_16x16x32_bf16 with rows = window points and
+//                 columns = queries; fp32 features enter as bf16 hi + lo and
 //                 the three significant partial products are accumulated in
 //                 fp32 (hi*hi + hi*lo + lo*hi), or hi*hi alone in bf16 mode.
 //   epilogue    : S goes to LDS as [pt][query]; each query reads the 2x2 stencil
 //                 of its own (2r+2)^2 sub-window and writes its (2r+1)^2 taps.
-// Window points outside the level enter as zero fragments, which is the zero
+// Window points outside the level are staged as zeros, which is the zero
 // padding of the sampling rule.  The query features are re-read per level from
 // L2, so HBM sees them once per lookup.
 #include "corr_internal.h"
@@ -52,9 +51,10 @@ struct Geo {
     static constexpr int NWB = (NPTS + 15) / 16;          // 16-point row blocks
     static constexpr int WBW = (NWB + 3) / 4;             // row blocks per wave
     static constexpr int ROWS = NWB * 16;
-    static constexpr int STAGE_BYTES = CORR_GROUP * ROWB;
+    static constexpr int STAGE_BYTES = (ROWS + CORR_GROUP) * ROWB;
     static constexpr int S_BYTES = ROWS * CORR_GROUP * 4;
     static constexpr int UNION_BYTES = cmax(STAGE_BYTES, S_BYTES);
+    static constexpr int WIN_ITERS = (NPTS * 8 + 255) / 256;
 };
 constexpr int UNION_BYTES = cmax(cmax(Geo<0>::UNION_BYTES, Geo<1>::UNION_BYTES),
                                  cmax(Geo<2>::UNION_BYTES, Geo<3>::UNION_BYTES));
@@ -64,14 +64,15 @@ constexpr int LDS_BYTES = UNION_BYTES + META_BYTES;
 struct ItemCtx {
     int b, u, v, n;          // batch item, absolute cell coordinates, queries in the group
     int tid, lane, wave;
-    int qoff[2];             // element offset (chunk 0) of the two query pieces this thread stages, or -1
+    int qoff[2];             // this thread's two 16-byte pieces of the query rows (element offset or -1)
 };
 
 template <int LVL, bool THREE>
 __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
                                            const int* q_pix, const float* q_cx, const float* q_cy) {
     using G = Geo<LVL>;
-    unsigned char* qry = smem;                               // 64 x ROWB, this chunk's query rows
+    unsigned char* win = smem;                               // ROWS x ROWB
+    unsigned char* qry = smem + G::ROWS * ROWB;              // 64 x ROWB
     float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging area
     const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
     const int xs = ((c.u << CORR_LOG_CX) >> LVL) - R;        // window origin in level pixels
@@ -92,21 +93,21 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         return;
     }
 
-    // Window operand: read from global memory straight into MFMA fragments.  Lane (p, g) =
-    // (lane % 16, lane / 16) holds window point wb*16 + p, channels 8g..8g+7 of the chunk: 16 bytes
-    // of that pixel's 128-byte chunk record (64 B hi, 64 B lo).  A record is read by this wave only,
-    // hi then lo, so every line comes from L2 once.
-    const int p16 = lane & 15, g4 = lane >> 4;
-    int woff[G::WBW];           // element offset of this lane's piece at chunk 0, or -1 (padding)
+    // rows NPTS..ROWS-1 of the window never receive data: keep them zero
+    for (int i = tid; i < (G::ROWS - G::NPTS) * (ROWB / 16); i += 256)
+        reinterpret_cast<uint4*>(win + G::NPTS * ROWB)[i] = make_uint4(0, 0, 0, 0);
+
+    // staging plan: the same (point, 16-byte piece) per thread for every chunk
+    int goff[G::WIN_ITERS];
 #pragma unroll
-    for (int i = 0; i < G::WBW; ++i) {
-        const int pt = (wave + 4 * i) * 16 + p16;
-        woff[i] = -1;
+    for (int it = 0; it < G::WIN_ITERS; ++it) {
+        const int idx = it * 256 + tid;
+        const int pt = idx >> 3, piece = idx & 7;
+        goff[it] = -1;
         if (pt < G::NPTS) {
             const int wy = pt / G::WSX, wx = pt - wy * G::WSX;
             const int y = ys + wy, x = xs + wx;
-            if (y >= 0 && y < Hl && x >= 0 && x < Wl)
-                woff[i] = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * 64 + g4 * 8;
+            if (y >= 0 && y < Hl && x >= 0 && x < Wl) goff[it] = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * 64 + piece * 8;
         }
     }
 
@@ -117,19 +118,17 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int nqf = (c.n + 15) >> 4;
-    const int frag_off = p16 * ROWB + g4 * 16;
+    const int frag_off = (lane & 15) * ROWB + (lane >> 4) * 16;
 
-    uint4 wh[G::WBW], wl[G::WBW], qv[2];
+    // global -> registers for chunk 0; inside the loop the next chunk's loads are
+    // issued right after the LDS stores so that they fly under the MFMAs
+    uint4 wv[G::WIN_ITERS], qv[2];
     auto load_chunk = [&](int kc) {
-        const uint16_t* src = a.f2s + (size_t)kc * a.f2_stride;
-#pragma unroll
-        for (int i = 0; i < G::WBW; ++i) {
-            wh[i] = woff[i] >= 0 ? *reinterpret_cast<const uint4*>(src + woff[i]) : make_uint4(0, 0, 0, 0);
-            if (THREE)
-                wl[i] = woff[i] >= 0 ? *reinterpret_cast<const uint4*>(src + woff[i] + 32) : make_uint4(0, 0, 0, 0);
-        }
-        // query rows: thread = (query, 16-byte piece of its chunk record)
+        const uint16_t* f2c = a.f2s + (size_t)kc * a.f2_stride;
         const uint16_t* f1c = a.f1s + (size_t)kc * a.f1_stride;
+#pragma unroll
+        for (int it = 0; it < G::WIN_ITERS; ++it)
+            wv[it] = goff[it] >= 0 ? *reinterpret_cast<const uint4*>(f2c + goff[it]) : make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int it = 0; it < 2; ++it)
             qv[it] = c.qoff[it] >= 0 ? *reinterpret_cast<const uint4*>(f1c + c.qoff[it]) : make_uint4(0, 0, 0, 0);
@@ -137,20 +136,20 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     load_chunk(0);
 
     for (int kc = 0; kc < a.NC; ++kc) {
-        if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk's query rows
+        if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk
+#pragma unroll
+        for (int it = 0; it < G::WIN_ITERS; ++it) {
+            const int idx = it * 256 + tid;
+            if ((idx >> 3) < G::NPTS)
+                *reinterpret_cast<uint4*>(win + (idx >> 3) * ROWB + (idx & 7) * 16) = wv[it];
+        }
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int idx = it * 256 + tid;
             *reinterpret_cast<uint4*>(qry + (idx >> 3) * ROWB + (idx & 7) * 16) = qv[it];
         }
         __syncthreads();
-        bf16x8 ch[G::WBW], cl[G::WBW];          // this chunk's window fragments
-#pragma unroll
-        for (int i = 0; i < G::WBW; ++i) {
-            ch[i] = __builtin_bit_cast(bf16x8, wh[i]);
-            if (THREE) cl[i] = __builtin_bit_cast(bf16x8, wl[i]);
-        }
-        if (kc + 1 < a.NC) load_chunk(kc + 1);  // next chunk flies under this chunk's MFMAs
+        if (kc + 1 < a.NC) load_chunk(kc + 1);
 
         bf16x8 qh[4], ql[4];
 #pragma unroll
@@ -160,15 +159,19 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         }
 #pragma unroll
         for (int i = 0; i < G::WBW; ++i) {
-            if (wave + 4 * i < G::NWB) {
+            const int wb = wave + 4 * i;
+            if (wb < G::NWB) {
+                const bf16x8 wh = *reinterpret_cast<const bf16x8*>(win + wb * 16 * ROWB + frag_off);
+                bf16x8 wl;
+                if (THREE) wl = *reinterpret_cast<const bf16x8*>(win + wb * 16 * ROWB + frag_off + 64);
 #pragma unroll
                 for (int qf = 0; qf < 4; ++qf) {
                     if (qf < nqf) {
                         if (THREE) {
-                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cl[i], qh[qf], acc[i][qf], 0, 0, 0);
-                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ch[i], ql[qf], acc[i][qf], 0, 0, 0);
+                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl, qh[qf], acc[i][qf], 0, 0, 0);
+                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh, ql[qf], acc[i][qf], 0, 0, 0);
                         }
-                        acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ch[i], qh[qf], acc[i][qf], 0, 0, 0);
+                        acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh, qh[qf], acc[i][qf], 0, 0, 0);
                     }
                 }
             }

@@ -283,9 +283,18 @@ corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, vo
     if (!pyr || !stats) return CORR_ERR_INVALID_ARG;
     if (!(pyr->reps & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
     long long h[CORR_NSTATS];
+    int hn[4];
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (launch_bin_stats(pyr, s) != hipSuccess) return CORR_ERR_HIP;
     if (hipMemcpyAsync(h, pyr->stats, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
+    if (hipMemcpyAsync(hn, pyr->n_items, sizeof(hn), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return CORR_ERR_HIP;
+    h[0] = hn[0];
+    h[1] = (long long)pyr->B * pyr->H * pyr->W * pyr->L;
+    h[3] = h[4] = 0;
+    long long ql = 0;
+    for (int l = 0; l < 4; ++l) { h[3] += h[8 + 4 * l + 1]; h[4] += h[8 + 4 * l + 2]; ql += h[8 + 4 * l + 3]; }
+    h[2] = h[1] - ql;
     stats->items = h[0]; stats->query_levels = h[1]; stats->null_query_levels = h[2];
     stats->mma_point_queries = h[3]; stats->used_point_queries = h[4];
     for (int l = 0; l < 4; ++l) {
@@ -295,6 +304,11 @@ corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, vo
         stats->level_queries[l] = h[8 + 4 * l + 3];
     }
     return CORR_OK;
+}
+
+corr_status corr_copy_f32(float* dst, const float* src, size_t n, void* stream) {
+    if (!dst || !src || (n & 3) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return CORR_ERR_INVALID_ARG;
+    return launch_copy_f32(dst, src, n, static_cast<hipStream_t>(stream)) == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 
 corr_status corr_profile_enable(corr_pyramid* pyr, int enable) {

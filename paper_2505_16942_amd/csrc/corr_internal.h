@@ -64,7 +64,7 @@ struct corr_pyramid {
     int* q_rank;                   // [B*H*W] slot within the cell
     int* perm;                     // [B*H*W] queries sorted by cell
     int4* items;                   // [max_items] {cell id, first perm index, n queries, 0}
-    int* n_items;                  // [1]
+    int* n_items;                  // [4]: items, binned queries
     long long* stats;              // [CORR_NSTATS]: 0..4 totals, 8+4*l+{0,1,2,3} per level
     // CORR_MODE_FULLVOLUME cache
     float* vol[CORR_MAX_L];        // [B][H*W][H_l*W_l]
@@ -93,7 +93,9 @@ static inline void corr_fill_grid(CellGrid* g, int H, int W, int L, int r) {
 // launchers (each enqueues on `s` and returns hipGetLastError())
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
                                  uint16_t* split, float* const* nhwc, hipStream_t s);
+hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s);
 hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipStream_t s);
+hipError_t launch_bin_stats(corr_pyramid* p, hipStream_t s);
 hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
 hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
 hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s);

@@ -125,7 +125,19 @@ __global__ __launch_bounds__(256) void build_features_kernel(BuildArgs a) {
     }
 }
 
+__global__ __launch_bounds__(256) void copy_f32_kernel(float4* __restrict__ dst, const float4* __restrict__ src, size_t n4) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
 }  // namespace
+
+hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s) {
+    // whole float4s only; the measurement buffers are multiples of 4 floats
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(256 * 16), dim3(256), 0, s, reinterpret_cast<float4*>(dst),
+                       reinterpret_cast<const float4*>(src), n / 4);
+    return hipGetLastError();
+}
 
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
                                  uint16_t* split, float* const* nhwc, hipStream_t s) {
