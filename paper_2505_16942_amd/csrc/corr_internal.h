@@ -7,9 +7,13 @@
 
 #define CORR_MAX_L 4
 #define CORR_CHUNK 32          // channels per chunk plane of the split representation
-#define CORR_GROUP 64          // queries per work item
+#ifndef CORR_GROUP
+#define CORR_GROUP 64          // queries per work item (64 or 128)
+#endif
 #define CORR_R 4               // radius the block kernels are built for
+#ifndef CORR_LOG_CX
 #define CORR_LOG_CX 3          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
+#endif
 #define CORR_LOG_CY 3
 #define CORR_COORD_LIMIT 1048576.0f
 #define CORR_NSTATS 24
