@@ -7,7 +7,7 @@
 // each) x 4 window quarters.
 //   contraction : S_l[pt][q] = <f2_l(window point pt), f1(query q)> over D, in
 //                 32-channel chunks staged through LDS (coalesced 16-byte loads of
-//                 128-byte records per pixel and chunk), on
+//                 128-byte records per pixel and chunk; bf16 mode loads only the hi half), on
 //                 v_mfma_f32_16x16x32_bf16 with rows = window points and columns =
 //                 queries; fp32 features enter as bf16 hi + lo and the three
 //                 significant partial products are accumulated in fp32
@@ -25,7 +25,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int ROWB = 144;   // LDS bytes per staged row: 64 B hi + 64 B lo + 16 B pad (conflict-free b128 reads)
 constexpr int R = CORR_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 constexpr int NQH = CORR_GROUP / 64;     // query halves
@@ -49,8 +48,10 @@ struct BlockArgs {
 
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
-template <int LVL>
+template <int LVL, bool THREE = true>
 struct Geo {
+    static constexpr int PPR = THREE ? 8 : 4;             // 16-byte pieces staged per row (hi, and lo if used)
+    static constexpr int ROWB = PPR * 16 + 16;            // LDS bytes per staged row; the pad makes b128 reads conflict-free
     static constexpr int CXL = cmax(CX >> LVL, 1), CYL = cmax(CY >> LVL, 1);
     static constexpr int WSX = CXL + K, WSY = CYL + K;   // window sides
     static constexpr int NPTS = WSX * WSY;
@@ -61,7 +62,9 @@ struct Geo {
     static constexpr int STAGE_BYTES = STAGE_ROWS * ROWB;
     static constexpr int S_BYTES = ROWS * 64 * 4;         // one query half
     static constexpr int UNION_BYTES = cmax(STAGE_BYTES, S_BYTES);
-    static constexpr int ITERS = (STAGE_ROWS * 8 + NT - 1) / NT;   // 16-byte pieces per thread and chunk
+    static constexpr int ITERS = (STAGE_ROWS * PPR + NT - 1) / NT;   // 16-byte pieces per thread and chunk
+    __device__ static int row_of(int idx) { return idx / PPR; }
+    __device__ static int piece_of(int idx) { return idx % PPR; }
 };
 constexpr int UNION_BYTES = cmax(cmax(Geo<0>::UNION_BYTES, Geo<1>::UNION_BYTES),
                                  cmax(Geo<2>::UNION_BYTES, Geo<3>::UNION_BYTES));
@@ -84,7 +87,8 @@ __device__ __forceinline__ void window_origin(const ItemCtx& c, int& xs, int& ys
 
 template <int LVL, bool THREE>
 __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem) {
-    using G = Geo<LVL>;
+    using G = Geo<LVL, THREE>;
+    constexpr int ROWB = G::ROWB;
     unsigned char* rows = smem;                              // ROWS window rows, then CORR_GROUP query rows
     float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging area
     const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
@@ -109,7 +113,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
 #pragma unroll
     for (int it = 0; it < G::ITERS; ++it) {
         const int idx = it * NT + tid;
-        const int row = idx >> 3, piece = idx & 7;
+        const int row = G::row_of(idx), piece = G::piece_of(idx);   // pieces 0..3: hi record, 4..7: lo record
         int off = -1;
         if (row < G::NPTS) {
             const int wy = row / G::WSX, wx = row - wy * G::WSX;
@@ -139,7 +143,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     auto load_chunk = [&](int kc) {
 #pragma unroll
         for (int it = 0; it < G::ITERS; ++it) {
-            const bool is_q = (it * NT + tid) >= G::ROWS * 8;
+            const bool is_q = G::row_of(it * NT + tid) >= G::ROWS;
             const uint16_t* base = is_q ? a.f1s + (size_t)kc * a.f1_stride : a.f2s + (size_t)kc * a.f2_stride;
             sv[it] = goff[it] >= 0 ? *reinterpret_cast<const uint4*>(base + goff[it]) : make_uint4(0, 0, 0, 0);
         }
@@ -151,8 +155,8 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
 #pragma unroll
         for (int it = 0; it < G::ITERS; ++it) {
             const int idx = it * NT + tid;
-            if ((idx >> 3) < G::STAGE_ROWS)
-                *reinterpret_cast<uint4*>(rows + (idx >> 3) * ROWB + (idx & 7) * 16) = sv[it];
+            if (G::row_of(idx) < G::STAGE_ROWS)
+                *reinterpret_cast<uint4*>(rows + G::row_of(idx) * ROWB + G::piece_of(idx) * 16) = sv[it];
         }
         __syncthreads();
         if (kc + 1 < a.NC) load_chunk(kc + 1);
