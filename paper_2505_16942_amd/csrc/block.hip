@@ -2,20 +2,22 @@
 // Computation" and "Sparse Volume Sampling"; fused as in "Fused Implementation":
 // the computed block lives only in registers and LDS).
 //
-// One workgroup = one work item = (target cell, up to CORR_GROUP of its queries),
-// processed level after level.  Waves form a grid of NQH query halves (64 queries
-// each) x 4 window quarters.
-//   contraction : S_l[pt][q] = <f2_l(window point pt), f1(query q)> over D, in
-//                 32-channel chunks staged through LDS (coalesced 16-byte loads of
-//                 128-byte records per pixel and chunk; bf16 mode loads only the hi half), on
-//                 v_mfma_f32_16x16x32_bf16 with rows = window points and columns =
-//                 queries; fp32 features enter as bf16 hi + lo and the three
+// One workgroup = one work item = (target cell, up to 64 of its queries), processed
+// level after level by four waves.  Wave w owns queries 16w .. 16w+15 of the item.
+//   queries     : each wave loads the bf16 hi (and lo) fragments of its 16 queries for all
+//                 D channels once per item, straight from global memory into the MFMA
+//                 B-operand layout, and keeps them in registers for all levels.
+//   contraction : S_l[pt][q] = <f2_l(window point pt), f1(query q)> over D.  The window is
+//                 staged through LDS in 32-channel chunks (coalesced 16-byte loads of
+//                 128-byte records per pixel and chunk; bf16 mode loads only the hi half);
+//                 every wave multiplies all 16-point row blocks of the window with its own
+//                 query fragment on v_mfma_f32_16x16x32_bf16 (rows = window points,
+//                 columns = queries).  fp32 features enter as bf16 hi + lo and the three
 //                 significant partial products are accumulated in fp32
-//                 (hi*hi + hi*lo + lo*hi), or hi*hi alone in bf16 mode.  The loads
-//                 of the next chunk fly under the MFMAs of the current one.
-//   epilogue    : for one query half at a time S_l goes to LDS as [pt][query]; each
-//                 query reads the 2x2 stencil of its own (2r+2)^2 sub-window and
-//                 writes its (2r+1)^2 taps.
+//                 (hi*hi + hi*lo + lo*hi), or hi*hi alone in bf16 mode.  The loads of the
+//                 next chunk fly under the MFMAs of the current one.
+//   epilogue    : S_l goes to LDS as [pt][query]; each query reads the 2x2 stencil of its
+//                 own (2r+2)^2 sub-window and writes its (2r+1)^2 taps.
 // Window points outside the level are staged as zeros, which is the zero
 // padding of the sampling rule.
 #include "corr_internal.h"
@@ -27,9 +29,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int R = CORR_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
-constexpr int NQH = CORR_GROUP / 64;     // query halves
-constexpr int NW = 4 * NQH, NT = 64 * NW;
-static_assert(CORR_GROUP == 64 || CORR_GROUP == 128, "work items hold 64 or 128 queries");
+constexpr int NW = 4, NT = 64 * NW;
+constexpr int NCMAX = CORR_BLOCK_MAX_D / CORR_CHUNK;   // chunks of query fragments a wave can hold
+static_assert(CORR_GROUP == 64, "work items hold 64 queries: 16 per wave");
 
 struct BlockArgs {
     const uint16_t* f1s;                 // [NC][B*HW][64]
@@ -56,11 +58,10 @@ struct Geo {
     static constexpr int WSX = CXL + K, WSY = CYL + K;   // window sides
     static constexpr int NPTS = WSX * WSY;
     static constexpr int NWB = (NPTS + 15) / 16;          // 16-point row blocks
-    static constexpr int WBW = (NWB + 3) / 4;             // row blocks per window quarter
     static constexpr int ROWS = NWB * 16;
-    static constexpr int STAGE_ROWS = ROWS + CORR_GROUP;  // window rows, then query rows
+    static constexpr int STAGE_ROWS = ROWS;
     static constexpr int STAGE_BYTES = STAGE_ROWS * ROWB;
-    static constexpr int S_BYTES = ROWS * 64 * 4;         // one query half
+    static constexpr int S_BYTES = ROWS * 64 * 4;
     static constexpr int UNION_BYTES = cmax(STAGE_BYTES, S_BYTES);
     static constexpr int ITERS = (STAGE_ROWS * PPR + NT - 1) / NT;   // 16-byte pieces per thread and chunk
     __device__ static int row_of(int idx) { return idx / PPR; }
@@ -86,16 +87,16 @@ __device__ __forceinline__ void window_origin(const ItemCtx& c, int& xs, int& ys
 }
 
 template <int LVL, bool THREE>
-__device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem) {
+__device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
+                                           const bf16x8 (&qhi)[NCMAX], const bf16x8 (&qlo)[NCMAX]) {
     using G = Geo<LVL, THREE>;
     constexpr int ROWB = G::ROWB;
-    unsigned char* rows = smem;                              // ROWS window rows, then CORR_GROUP query rows
+    unsigned char* rows = smem;                              // ROWS window rows
     float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging area
     const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
     const int tid = c.tid, lane = c.lane, wave = c.wave;
-    const int wq = wave & 3, qh = wave >> 2;                 // window quarter, query half of this wave
     float* o_lvl = a.out + ((size_t)(c.b * a.L + LVL) * KK) * a.HW;
 
     const bool touches = xs + G::WSX - 1 >= 0 && xs <= Wl - 1 && ys + G::WSY - 1 >= 0 && ys <= Hl - 1;
@@ -108,7 +109,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     }
 
     // staging plan: the same (row, 16-byte piece) per thread for every chunk.  goff = element
-    // offset at chunk 0 (window rows index f2s, query rows index f1s) or -1 for zero rows.
+    // offset into f2s at chunk 0, or -1 for zero rows.
     int goff[G::ITERS];
 #pragma unroll
     for (int it = 0; it < G::ITERS; ++it) {
@@ -119,124 +120,107 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
             const int wy = row / G::WSX, wx = row - wy * G::WSX;
             const int y = ys + wy, x = xs + wx;
             if (y >= 0 && y < Hl && x >= 0 && x < Wl) off = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * 64;
-        } else if (row >= G::ROWS && row < G::STAGE_ROWS) {
-            const int pix = c.q_pix[row - G::ROWS];
-            if (pix >= 0) off = (c.b * a.HW + pix) * 64;
         }
         goff[it] = off < 0 ? -1 : off + piece * 8;
     }
 
-    f32x4 acc[G::WBW][4];
+    f32x4 acc[G::NWB];
 #pragma unroll
-    for (int i = 0; i < G::WBW; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < G::NWB; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int nh = min(max(c.n - 64 * qh, 0), 64);           // queries in this wave's half
-    const int nqf = (nh + 15) >> 4;
+    const bool active = wave * 16 < c.n;                     // this wave has queries
     const int frag_off = (lane & 15) * ROWB + (lane >> 4) * 16;
-    const unsigned char* qry = rows + (G::ROWS + 64 * qh) * ROWB;
 
     // global -> registers for chunk 0; inside the loop the next chunk's loads are
     // issued right after the LDS stores so that they fly under the MFMAs
     uint4 sv[G::ITERS];
     auto load_chunk = [&](int kc) {
+        const uint16_t* base = a.f2s + (size_t)kc * a.f2_stride;
 #pragma unroll
-        for (int it = 0; it < G::ITERS; ++it) {
-            const bool is_q = G::row_of(it * NT + tid) >= G::ROWS;
-            const uint16_t* base = is_q ? a.f1s + (size_t)kc * a.f1_stride : a.f2s + (size_t)kc * a.f2_stride;
+        for (int it = 0; it < G::ITERS; ++it)
             sv[it] = goff[it] >= 0 ? *reinterpret_cast<const uint4*>(base + goff[it]) : make_uint4(0, 0, 0, 0);
-        }
     };
     load_chunk(0);
 
-    for (int kc = 0; kc < a.NC; ++kc) {
-        if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk
 #pragma unroll
-        for (int it = 0; it < G::ITERS; ++it) {
-            const int idx = it * NT + tid;
-            if (G::row_of(idx) < G::STAGE_ROWS)
-                *reinterpret_cast<uint4*>(rows + G::row_of(idx) * ROWB + G::piece_of(idx) * 16) = sv[it];
-        }
-        __syncthreads();
-        if (kc + 1 < a.NC) load_chunk(kc + 1);
-
-        bf16x8 qhi[4], qlo[4];
+    for (int kc = 0; kc < NCMAX; ++kc) {
+        if (kc < a.NC) {                            // uniform
+            if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk
 #pragma unroll
-        for (int qf = 0; qf < 4; ++qf) {
-            qhi[qf] = *reinterpret_cast<const bf16x8*>(qry + qf * 16 * ROWB + frag_off);
-            if (THREE) qlo[qf] = *reinterpret_cast<const bf16x8*>(qry + qf * 16 * ROWB + frag_off + 64);
-        }
+            for (int it = 0; it < G::ITERS; ++it) {
+                const int idx = it * NT + tid;
+                if (G::row_of(idx) < G::STAGE_ROWS)
+                    *reinterpret_cast<uint4*>(rows + G::row_of(idx) * ROWB + G::piece_of(idx) * 16) = sv[it];
+            }
+            __syncthreads();
+            if (kc + 1 < a.NC) load_chunk(kc + 1);
+            if (active) {
+                // window fragments are read two row blocks ahead of the MFMAs that use them
+                constexpr int PF = 2;
+                bf16x8 wh[G::NWB + PF], wl[G::NWB + PF];
 #pragma unroll
-        for (int i = 0; i < G::WBW; ++i) {
-            const int wb = wq + 4 * i;
-            if (wb < G::NWB) {
-                const bf16x8 wh = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * ROWB + frag_off);
-                bf16x8 wl;
-                if (THREE) wl = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * ROWB + frag_off + 64);
+                for (int wb = 0; wb < PF; ++wb) {
+                    wh[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * ROWB + frag_off);
+                    if (THREE) wl[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * ROWB + frag_off + 64);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 * PF : PF, 0);
 #pragma unroll
-                for (int qf = 0; qf < 4; ++qf) {
-                    if (qf < nqf) {
-                        if (THREE) {
-                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl, qhi[qf], acc[i][qf], 0, 0, 0);
-                            acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh, qlo[qf], acc[i][qf], 0, 0, 0);
-                        }
-                        acc[i][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh, qhi[qf], acc[i][qf], 0, 0, 0);
+                for (int wb = 0; wb < G::NWB; ++wb) {
+                    if (wb + PF < G::NWB) {
+                        wh[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * ROWB + frag_off);
+                        if (THREE) wl[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * ROWB + frag_off + 64);
                     }
+                    if (THREE) {
+                        acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[wb], qhi[kc], acc[wb], 0, 0, 0);
+                        acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[wb], qlo[kc], acc[wb], 0, 0, 0);
+                    }
+                    acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[wb], qhi[kc], acc[wb], 0, 0, 0);
+                    // keep this order in the schedule: the reads for block wb + PF, then the MFMAs of block wb
+                    if (wb + PF < G::NWB) __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 : 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, THREE ? 3 : 1, 0);
                 }
             }
         }
     }
     __syncthreads();                            // staging area is dead; S may overwrite it
 
-    // epilogue, one query half at a time
+    // lane holds query 16*wave + lane % 16, points 4*(lane/16)+v of every row block
+    if (active) {
 #pragma unroll
-    for (int h = 0; h < NQH; ++h) {
-        if (h * 64 >= c.n) break;               // uniform
-        if (qh == h) {
-            // lane holds query (lane % 16) of fragment qf, points 4*(lane/16)+v of its row blocks
+        for (int wb = 0; wb < G::NWB; ++wb)
 #pragma unroll
-            for (int i = 0; i < G::WBW; ++i) {
-                const int wb = wq + 4 * i;
-                if (wb < G::NWB) {
-#pragma unroll
-                    for (int qf = 0; qf < 4; ++qf)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            S[(wb * 16 + 4 * (lane >> 4) + v) * 64 + qf * 16 + (lane & 15)] = acc[i][qf][v] * a.scale;
-                }
-            }
-        }
-        __syncthreads();
-        // lane = query of this half; a wave takes half-columns of taps (x offset i, y offsets 0..4 or
-        // 5..8).  Along a column the x-interpolated value of each footprint row is reused by two taps.
-        const int q = h * 64 + lane;
-        if (q < c.n) {
-            const float inv = __uint_as_float((uint32_t)(127 - LVL) << 23);   // 2^-LVL
-            const float cxl = c.q_cx[q] * inv, cyl = c.q_cy[q] * inv;
-            const float flx = floorf(cxl), fly = floorf(cyl);
-            const float fx = cxl - flx, fy = cyl - fly;
-            const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
-            const float* s0 = S + (ry * G::WSX + rx) * 64 + lane;
-            float* o = o_lvl + c.q_pix[q];
-            for (int uidx = wave; uidx < 2 * K; uidx += NW) {
-                const int i = uidx >> 1, j0 = (uidx & 1) ? 5 : 0, j1 = (uidx & 1) ? K : 5;
-                const float* s = s0 + (j0 * G::WSX + i) * 64;
-                float hprev = s[0] + fx * (s[64] - s[0]);
-                for (int j = j0; j < j1; ++j) {
-                    s += G::WSX * 64;
-                    const float hcur = s[0] + fx * (s[64] - s[0]);
-                    o[(size_t)(i * K + j) * a.HW] = hprev + fy * (hcur - hprev);
-                    hprev = hcur;
-                }
-            }
-        }
-        __syncthreads();                        // S is dead
+            for (int v = 0; v < 4; ++v)
+                S[(wb * 16 + 4 * (lane >> 4) + v) * 64 + wave * 16 + (lane & 15)] = acc[wb][v] * a.scale;
     }
+    __syncthreads();
+    // lane = query; a wave takes half-columns of taps (x offset i, y offsets 0..4 or 5..8).
+    // Along a column the x-interpolated value of each footprint row is reused by two taps.
+    const int q = lane;
+    if (q < c.n) {
+        const float inv = __uint_as_float((uint32_t)(127 - LVL) << 23);   // 2^-LVL
+        const float cxl = c.q_cx[q] * inv, cyl = c.q_cy[q] * inv;
+        const float flx = floorf(cxl), fly = floorf(cyl);
+        const float fx = cxl - flx, fy = cyl - fly;
+        const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
+        const float* s0 = S + (ry * G::WSX + rx) * 64 + lane;
+        float* o = o_lvl + c.q_pix[q];
+        for (int uidx = wave; uidx < 2 * K; uidx += NW) {
+            const int i = uidx >> 1, j0 = (uidx & 1) ? 5 : 0, j1 = (uidx & 1) ? K : 5;
+            const float* s = s0 + (j0 * G::WSX + i) * 64;
+            float hprev = s[0] + fx * (s[64] - s[0]);
+            for (int j = j0; j < j1; ++j) {
+                s += G::WSX * 64;
+                const float hcur = s[0] + fx * (s[64] - s[0]);
+                o[(size_t)(i * K + j) * a.HW] = hprev + fy * (hcur - hprev);
+                hprev = hcur;
+            }
+        }
+    }
+    __syncthreads();                            // S is dead
 }
 
 template <bool THREE>
-__global__ __launch_bounds__(NT, NQH == 1 ? 2 : 1) void block_kernel(BlockArgs a) {
+__global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     int* q_pix = reinterpret_cast<int*>(smem + UNION_BYTES);
     float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP);
@@ -269,10 +253,28 @@ __global__ __launch_bounds__(NT, NQH == 1 ? 2 : 1) void block_kernel(BlockArgs a
     }
     __syncthreads();
 
-    level_pass<0, THREE>(a, c, smem);
-    if (a.L > 1) level_pass<1, THREE>(a, c, smem);
-    if (a.L > 2) level_pass<2, THREE>(a, c, smem);
-    if (a.L > 3) level_pass<3, THREE>(a, c, smem);
+    // query fragments of this wave: lane holds channels 8*(lane/16) .. +7 of every chunk of
+    // query 16*wave + lane%16 (the B operand of the MFMA); empty slots hold zeros
+    bf16x8 qhi[NCMAX], qlo[NCMAX];
+    {
+        const int pix = q_pix[c.wave * 16 + (c.lane & 15)];
+        const uint16_t* src = a.f1s + ((size_t)c.b * a.HW + max(pix, 0)) * 64 + (c.lane >> 4) * 8;
+#pragma unroll
+        for (int kc = 0; kc < NCMAX; ++kc) {
+            uint4 h = make_uint4(0, 0, 0, 0), l = make_uint4(0, 0, 0, 0);
+            if (kc < a.NC && pix >= 0) {
+                h = *reinterpret_cast<const uint4*>(src + (size_t)kc * a.f1_stride);
+                if (THREE) l = *reinterpret_cast<const uint4*>(src + (size_t)kc * a.f1_stride + 32);
+            }
+            qhi[kc] = __builtin_bit_cast(bf16x8, h);
+            qlo[kc] = __builtin_bit_cast(bf16x8, l);
+        }
+    }
+
+    level_pass<0, THREE>(a, c, smem, qhi, qlo);
+    if (a.L > 1) level_pass<1, THREE>(a, c, smem, qhi, qlo);
+    if (a.L > 2) level_pass<2, THREE>(a, c, smem, qhi, qlo);
+    if (a.L > 3) level_pass<3, THREE>(a, c, smem, qhi, qlo);
 }
 
 template <bool THREE>

@@ -7,9 +7,8 @@
 
 #define CORR_MAX_L 4
 #define CORR_CHUNK 32          // channels per chunk plane of the split representation
-#ifndef CORR_GROUP
-#define CORR_GROUP 64          // queries per work item (64 or 128)
-#endif
+#define CORR_GROUP 64          // queries per work item
+#define CORR_BLOCK_MAX_D 256   // the block kernel keeps a wave's query fragments for all D channels in registers
 #define CORR_R 4               // radius the block kernels are built for
 #ifndef CORR_LOG_CX
 #define CORR_LOG_CX 3          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
