@@ -10,12 +10,14 @@
 //   contraction : S_l[pt][q] = <f2_l(window point pt), f1(query q)> over D.  The window is
 //                 staged through LDS in 32-channel chunks (coalesced 16-byte loads of
 //                 128-byte records per pixel and chunk; bf16 mode loads only the hi half);
+//                 two LDS buffers alternate, one barrier per chunk, and a per-level ring of
+//                 one to three chunks in registers keeps loads in flight ahead of the staging;
 //                 every wave multiplies all 16-point row blocks of the window with its own
 //                 query fragment on v_mfma_f32_16x16x32_bf16 (rows = window points,
 //                 columns = queries).  fp32 features enter as bf16 hi + lo and the three
 //                 significant partial products are accumulated in fp32
-//                 (hi*hi + hi*lo + lo*hi), or hi*hi alone in bf16 mode.  The loads of the
-//                 next chunk fly under the MFMAs of the current one.
+//                 (hi*hi + hi*lo + lo*hi), or hi*hi alone in bf16 mode.  The first chunk of
+//                 the next level is fetched before the epilogue of the current one.
 //   epilogue    : S_l goes to LDS as [pt][query]; each query reads the 2x2 stencil of its
 //                 own (2r+2)^2 sub-window and writes its (2r+1)^2 taps.
 // Window points outside the level are staged as zeros, which is the zero
@@ -53,19 +55,27 @@ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 template <int LVL, bool THREE = true>
 struct Geo {
     static constexpr int PPR = THREE ? 8 : 4;             // 16-byte pieces staged per row (hi, and lo if used)
-    static constexpr int ROWB = PPR * 16 + 16;            // LDS bytes per staged row; the pad makes b128 reads conflict-free
+    static constexpr int ROWB = PPR * 16;                 // LDS bytes per staged row (pieces swizzled, no padding)
     static constexpr int CXL = cmax(CX >> LVL, 1), CYL = cmax(CY >> LVL, 1);
     static constexpr int WSX = CXL + K, WSY = CYL + K;   // window sides
     static constexpr int NPTS = WSX * WSY;
     static constexpr int NWB = (NPTS + 15) / 16;          // 16-point row blocks
     static constexpr int ROWS = NWB * 16;
-    static constexpr int STAGE_ROWS = ROWS;
-    static constexpr int STAGE_BYTES = STAGE_ROWS * ROWB;
+    static constexpr int BUF_BYTES = ROWS * ROWB;         // one staged chunk
     static constexpr int S_BYTES = ROWS * 64 * 4;
-    static constexpr int UNION_BYTES = cmax(STAGE_BYTES, S_BYTES);
-    static constexpr int ITERS = (STAGE_ROWS * PPR + NT - 1) / NT;   // 16-byte pieces per thread and chunk
+    static constexpr int UNION_BYTES = cmax(2 * BUF_BYTES, S_BYTES);
+    static constexpr int ITERS = (ROWS * PPR + NT - 1) / NT;   // 16-byte pieces per thread and chunk
+    // chunks kept in flight in registers ahead of the one being staged: the small windows of the
+    // coarse levels have short MFMA phases, so they need more loads in flight to cover the latency
+    static constexpr int PD = LVL == 0 ? 1 : (LVL == 1 ? 2 : 3);
     __device__ static int row_of(int idx) { return idx / PPR; }
     __device__ static int piece_of(int idx) { return idx % PPR; }
+    // LDS byte offset of piece `piece` of row `row`.  The piece slot is XOR-swizzled with the row
+    // so that the 16 rows x 16 bytes that a quarter wave reads for one MFMA fragment fall in 16
+    // different 4-bank groups.
+    __device__ static int lds_off(int row, int piece) {
+        return row * ROWB + ((piece ^ ((row / (16 / PPR)) & (PPR - 1))) << 4);
+    }
 };
 constexpr int UNION_BYTES = cmax(cmax(Geo<0>::UNION_BYTES, Geo<1>::UNION_BYTES),
                                  cmax(Geo<2>::UNION_BYTES, Geo<3>::UNION_BYTES));
@@ -80,6 +90,15 @@ struct ItemCtx {
     const float* q_cy;
 };
 
+// Per-thread staging state of one level: which 16-byte pieces of the window this thread
+// moves for every chunk, and a ring of PD chunks of them in registers.
+template <int LVL, bool THREE>
+struct Stage {
+    using G = Geo<LVL, THREE>;
+    int goff[G::ITERS];              // element offset into f2s at chunk 0, or -1 for a zero row
+    uint4 sv[G::PD][G::ITERS];
+};
+
 template <int LVL>
 __device__ __forceinline__ void window_origin(const ItemCtx& c, int& xs, int& ys) {
     xs = ((c.u << CORR_LOG_CX) >> LVL) - R;
@@ -87,33 +106,14 @@ __device__ __forceinline__ void window_origin(const ItemCtx& c, int& xs, int& ys
 }
 
 template <int LVL, bool THREE>
-__device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
-                                           const bf16x8 (&qhi)[NCMAX], const bf16x8 (&qlo)[NCMAX]) {
+__device__ __forceinline__ void plan(const BlockArgs& a, const ItemCtx& c, Stage<LVL, THREE>& st) {
     using G = Geo<LVL, THREE>;
-    constexpr int ROWB = G::ROWB;
-    unsigned char* rows = smem;                              // ROWS window rows
-    float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging area
     const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
-    const int tid = c.tid, lane = c.lane, wave = c.wave;
-    float* o_lvl = a.out + ((size_t)(c.b * a.L + LVL) * KK) * a.HW;
-
-    const bool touches = xs + G::WSX - 1 >= 0 && xs <= Wl - 1 && ys + G::WSY - 1 >= 0 && ys <= Hl - 1;
-    if (!touches) {             // uniform for the workgroup: this level's window is all padding
-        for (int q = lane; q < c.n; q += 64) {
-            float* o = o_lvl + c.q_pix[q];
-            for (int t = wave; t < KK; t += NW) o[(size_t)t * a.HW] = 0.f;
-        }
-        return;
-    }
-
-    // staging plan: the same (row, 16-byte piece) per thread for every chunk.  goff = element
-    // offset into f2s at chunk 0, or -1 for zero rows.
-    int goff[G::ITERS];
 #pragma unroll
     for (int it = 0; it < G::ITERS; ++it) {
-        const int idx = it * NT + tid;
+        const int idx = it * NT + c.tid;
         const int row = G::row_of(idx), piece = G::piece_of(idx);   // pieces 0..3: hi record, 4..7: lo record
         int off = -1;
         if (row < G::NPTS) {
@@ -121,7 +121,61 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
             const int y = ys + wy, x = xs + wx;
             if (y >= 0 && y < Hl && x >= 0 && x < Wl) off = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * 64;
         }
-        goff[it] = off < 0 ? -1 : off + piece * 8;
+        st.goff[it] = off < 0 ? -1 : off + piece * 8;
+    }
+}
+
+// global -> ring slot `slot` for chunk kc
+template <int LVL, bool THREE>
+__device__ __forceinline__ void fetch(const BlockArgs& a, Stage<LVL, THREE>& st, int slot, int kc) {
+    using G = Geo<LVL, THREE>;
+    const uint16_t* base = a.f2s + (size_t)kc * a.f2_stride;
+#pragma unroll
+    for (int it = 0; it < G::ITERS; ++it)
+        st.sv[slot][it] = st.goff[it] >= 0 ? *reinterpret_cast<const uint4*>(base + st.goff[it]) : make_uint4(0, 0, 0, 0);
+}
+
+// ring slot -> LDS buffer
+template <int LVL, bool THREE>
+__device__ __forceinline__ void stage(const Stage<LVL, THREE>& st, int slot, unsigned char* buf, int tid) {
+    using G = Geo<LVL, THREE>;
+#pragma unroll
+    for (int it = 0; it < G::ITERS; ++it) {
+        const int idx = it * NT + tid;
+        if (G::row_of(idx) < G::ROWS)
+            *reinterpret_cast<uint4*>(buf + G::lds_off(G::row_of(idx), G::piece_of(idx))) = st.sv[slot][it];
+    }
+}
+
+// One level of one work item.  On entry `st` holds the staging plan and chunk 0 in ring slot 0
+// (fetched before the previous level's epilogue); before its own epilogue the pass plans the next
+// level and fetches its chunk 0 into `nx`, so that those loads fly under the tap writes.
+template <int LVL, bool THREE, class NextStage>
+__device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
+                                           const bf16x8 (&qhi)[NCMAX], const bf16x8 (&qlo)[NCMAX],
+                                           Stage<LVL, THREE>& st, NextStage& nx) {
+    using G = Geo<LVL, THREE>;
+    constexpr int PD = G::PD;
+    float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging buffers
+    const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
+    int xs, ys;
+    window_origin<LVL>(c, xs, ys);
+    const int tid = c.tid, lane = c.lane, wave = c.wave;
+    float* o_lvl = a.out + ((size_t)(c.b * a.L + LVL) * KK) * a.HW;
+    auto prefetch_next = [&]() {
+        if constexpr (LVL + 1 < CORR_MAX_L) {
+            if (LVL + 1 < a.L) { plan<LVL + 1, THREE>(a, c, nx); fetch<LVL + 1, THREE>(a, nx, 0, 0); }
+        }
+    };
+
+    const bool touches = xs + G::WSX - 1 >= 0 && xs <= Wl - 1 && ys + G::WSY - 1 >= 0 && ys <= Hl - 1;
+    if (!touches) {             // uniform for the workgroup: this level's window is all padding
+        prefetch_next();
+        for (int q = lane; q < c.n; q += 64) {
+            float* o = o_lvl + c.q_pix[q];
+            for (int t = wave; t < KK; t += NW) o[(size_t)t * a.HW] = 0.f;
+        }
+        return;
     }
 
     f32x4 acc[G::NWB];
@@ -129,46 +183,43 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     for (int i = 0; i < G::NWB; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const bool active = wave * 16 < c.n;                     // this wave has queries
-    const int frag_off = (lane & 15) * ROWB + (lane >> 4) * 16;
+    // fragment read: lane holds channels 8*(lane/16)..+7 of row wb*16 + lane%16
+    const int frag_hi = G::lds_off(lane & 15, lane >> 4);
+    const int frag_lo = G::lds_off(lane & 15, 4 + (lane >> 4));
 
-    // global -> registers for chunk 0; inside the loop the next chunk's loads are
-    // issued right after the LDS stores so that they fly under the MFMAs
-    uint4 sv[G::ITERS];
-    auto load_chunk = [&](int kc) {
-        const uint16_t* base = a.f2s + (size_t)kc * a.f2_stride;
+    // two LDS buffers: while the MFMAs read chunk kc from one, chunk kc+1 is written to the
+    // other; one barrier per chunk.  Ring slot (k % PD) holds chunk k until it is staged.
 #pragma unroll
-        for (int it = 0; it < G::ITERS; ++it)
-            sv[it] = goff[it] >= 0 ? *reinterpret_cast<const uint4*>(base + goff[it]) : make_uint4(0, 0, 0, 0);
-    };
-    load_chunk(0);
+    for (int d = 1; d < PD; ++d)
+        if (d < a.NC) fetch<LVL, THREE>(a, st, d, d);
+    stage<LVL, THREE>(st, 0, smem, tid);
+    if (PD < a.NC) fetch<LVL, THREE>(a, st, 0, PD);
+    __syncthreads();
 
 #pragma unroll
     for (int kc = 0; kc < NCMAX; ++kc) {
         if (kc < a.NC) {                            // uniform
-            if (kc > 0) __syncthreads();            // everyone is done reading the previous chunk
-#pragma unroll
-            for (int it = 0; it < G::ITERS; ++it) {
-                const int idx = it * NT + tid;
-                if (G::row_of(idx) < G::STAGE_ROWS)
-                    *reinterpret_cast<uint4*>(rows + G::row_of(idx) * ROWB + G::piece_of(idx) * 16) = sv[it];
+            const unsigned char* rows = smem + (kc & 1) * G::BUF_BYTES;
+            unsigned char* other = smem + ((kc + 1) & 1) * G::BUF_BYTES;
+            if (PD > 1 && kc + 1 < a.NC) {          // the data is already here: stage first
+                stage<LVL, THREE>(st, (kc + 1) % PD, other, tid);
+                if (kc + 1 + PD < a.NC) fetch<LVL, THREE>(a, st, (kc + 1) % PD, kc + 1 + PD);
             }
-            __syncthreads();
-            if (kc + 1 < a.NC) load_chunk(kc + 1);
             if (active) {
                 // window fragments are read two row blocks ahead of the MFMAs that use them
                 constexpr int PF = 2;
                 bf16x8 wh[G::NWB + PF], wl[G::NWB + PF];
 #pragma unroll
                 for (int wb = 0; wb < PF; ++wb) {
-                    wh[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * ROWB + frag_off);
-                    if (THREE) wl[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * ROWB + frag_off + 64);
+                    wh[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * G::ROWB + frag_hi);
+                    if (THREE) wl[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * G::ROWB + frag_lo);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 * PF : PF, 0);
 #pragma unroll
                 for (int wb = 0; wb < G::NWB; ++wb) {
                     if (wb + PF < G::NWB) {
-                        wh[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * ROWB + frag_off);
-                        if (THREE) wl[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * ROWB + frag_off + 64);
+                        wh[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * G::ROWB + frag_hi);
+                        if (THREE) wl[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * G::ROWB + frag_lo);
                     }
                     if (THREE) {
                         acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[wb], qhi[kc], acc[wb], 0, 0, 0);
@@ -180,9 +231,15 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
                     __builtin_amdgcn_sched_group_barrier(0x008, THREE ? 3 : 1, 0);
                 }
             }
+            if (PD == 1 && kc + 1 < a.NC) {         // the loads had the MFMA phase to arrive
+                stage<LVL, THREE>(st, 0, other, tid);
+                if (kc + 2 < a.NC) fetch<LVL, THREE>(a, st, 0, kc + 2);
+            }
+            __syncthreads();
         }
     }
-    __syncthreads();                            // staging area is dead; S may overwrite it
+    // the staging buffers are dead; S may overwrite them
+    prefetch_next();
 
     // lane holds query 16*wave + lane % 16, points 4*(lane/16)+v of every row block
     if (active) {
@@ -241,6 +298,11 @@ __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     c.u += a.g.u_min; c.v += a.g.v_min;
     c.q_pix = q_pix; c.q_cx = q_cx; c.q_cy = q_cy;
 
+    // level 0's first chunk starts to move before anything else
+    Stage<0, THREE> s0;
+    plan<0, THREE>(a, c, s0);
+    fetch<0, THREE>(a, s0, 0, 0);
+
     if (c.tid < CORR_GROUP) {
         int pix = -1;
         float cx = 0.f, cy = 0.f;
@@ -271,10 +333,17 @@ __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
         }
     }
 
-    level_pass<0, THREE>(a, c, smem, qhi, qlo);
-    if (a.L > 1) level_pass<1, THREE>(a, c, smem, qhi, qlo);
-    if (a.L > 2) level_pass<2, THREE>(a, c, smem, qhi, qlo);
-    if (a.L > 3) level_pass<3, THREE>(a, c, smem, qhi, qlo);
+    Stage<1, THREE> s1;
+    level_pass<0, THREE>(a, c, smem, qhi, qlo, s0, s1);
+    if (a.L > 1) {
+        Stage<2, THREE> s2;
+        level_pass<1, THREE>(a, c, smem, qhi, qlo, s1, s2);
+        if (a.L > 2) {
+            Stage<3, THREE> s3;
+            level_pass<2, THREE>(a, c, smem, qhi, qlo, s2, s3);
+            if (a.L > 3) level_pass<3, THREE>(a, c, smem, qhi, qlo, s3, s3);
+        }
+    }
 }
 
 template <bool THREE>
