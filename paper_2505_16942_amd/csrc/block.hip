@@ -250,8 +250,9 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
                 S[(wb * 16 + 4 * (lane >> 4) + v) * 64 + wave * 16 + (lane & 15)] = acc[wb][v] * a.scale;
     }
     __syncthreads();
-    // lane = query; a wave takes half-columns of taps (x offset i, y offsets 0..4 or 5..8).
-    // Along a column the x-interpolated value of each footprint row is reused by two taps.
+    // lane = query; wave 0 takes tap columns (x offsets) 0..2, waves 1..3 two columns each.  A
+    // footprint column is read from LDS once (all 2r+2 rows at once, so the reads overlap) and
+    // serves as the right neighbour of one tap column and the left neighbour of the next.
     const int q = lane;
     if (q < c.n) {
         const float inv = __uint_as_float((uint32_t)(127 - LVL) << 23);   // 2^-LVL
@@ -259,18 +260,26 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         const float flx = floorf(cxl), fly = floorf(cyl);
         const float fx = cxl - flx, fy = cyl - fly;
         const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
-        const float* s0 = S + (ry * G::WSX + rx) * 64 + lane;
-        float* o = o_lvl + c.q_pix[q];
-        for (int uidx = wave; uidx < 2 * K; uidx += NW) {
-            const int i = uidx >> 1, j0 = (uidx & 1) ? 5 : 0, j1 = (uidx & 1) ? K : 5;
-            const float* s = s0 + (j0 * G::WSX + i) * 64;
-            float hprev = s[0] + fx * (s[64] - s[0]);
-            for (int j = j0; j < j1; ++j) {
-                s += G::WSX * 64;
-                const float hcur = s[0] + fx * (s[64] - s[0]);
-                o[(size_t)(i * K + j) * a.HW] = hprev + fy * (hcur - hprev);
+        const int i0 = wave == 0 ? 0 : 2 * wave + 1, i1 = 2 * wave + 3;   // 0..3, 3..5, 5..7, 7..9
+        const float* s = S + (ry * G::WSX + rx + i0) * 64 + lane;
+        float* o = o_lvl + c.q_pix[q] + (size_t)(i0 * K) * a.HW;
+        float left[K + 1], right[K + 1];
+#pragma unroll
+        for (int j = 0; j <= K; ++j) left[j] = s[j * G::WSX * 64];
+        for (int i = i0; i < i1; ++i) {
+            s += 64;
+#pragma unroll
+            for (int j = 0; j <= K; ++j) right[j] = s[j * G::WSX * 64];
+            float hprev = left[0] + fx * (right[0] - left[0]);
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                const float hcur = left[j + 1] + fx * (right[j + 1] - left[j + 1]);
+                o[(size_t)j * a.HW] = hprev + fy * (hcur - hprev);
                 hprev = hcur;
             }
+#pragma unroll
+            for (int j = 0; j <= K; ++j) left[j] = right[j];
+            o += (size_t)K * a.HW;
         }
     }
     __syncthreads();                            // S is dead
