@@ -32,6 +32,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int R = CORR_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 constexpr int NW = 4, NT = 64 * NW;
+constexpr int XCD_RUN = 128;
 constexpr int NCMAX = CORR_BLOCK_MAX_D / CORR_CHUNK;   // chunks of query fragments a wave can hold
 static_assert(CORR_GROUP == 64, "work items hold 64 queries: 16 per wave");
 
@@ -292,13 +293,15 @@ __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP);
     float* q_cy = q_cx + CORR_GROUP;
 
-    // XCD-aware item choice: workgroup w runs on XCD w % 8; give each XCD one
-    // contiguous eighth of the items (neighbouring cells share window rows and
-    // columns, so they should share an L2).
+    // XCD-aware item choice: workgroup w runs on XCD w % 8.  Items are dealt to the XCDs in runs
+    // of consecutive items (neighbouring cells share window rows and columns, so they should
+    // share an L2), round robin, so that cheap border regions do not all land on the same XCD.
+    // About 16 runs per XCD, at most XCD_RUN items each.
     const int n_items = *a.n_items;
-    const int per_xcd = (n_items + 7) >> 3;
-    const int k = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || k >= n_items) return;
+    const int run = min(max(n_items >> 7, 8), XCD_RUN);
+    const int j = blockIdx.x >> 3;
+    const int k = ((j / run) * 8 + (blockIdx.x & 7)) * run + j % run;
+    if (k >= n_items) return;
     const int4 item = a.items[k];
     ItemCtx c;
     c.tid = threadIdx.x; c.lane = c.tid & 63; c.wave = c.tid >> 6;
@@ -372,7 +375,7 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
     for (int l = 0; l < CORR_MAX_L; ++l) { a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; a.pix_base[l] = p->f2_pix_base[l]; }
     a.f1_stride = p->B * p->H * p->W * 64; a.f2_stride = p->f2_pix_total * 64;
     a.scale = 1.0f / sqrtf((float)p->D);
-    const int grid = ((p->max_items + 7) / 8) * 8;
+    const int grid = (p->max_items + 8 * XCD_RUN - 1) / (8 * XCD_RUN) * (8 * XCD_RUN);
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), LDS_BYTES, s, a);
     return hipGetLastError();
 }
