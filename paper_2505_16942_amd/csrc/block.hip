@@ -6,7 +6,8 @@
 // level after level by four waves.  Wave w owns queries 16w .. 16w+15 of the item.
 //   queries     : each wave loads the bf16 hi (and lo) fragments of its 16 queries for all
 //                 D channels once per item, straight from global memory into the MFMA
-//                 B-operand layout, and keeps them in registers for all levels.
+//                 B-operand layout, and keeps them in registers for all levels (D <= 256; a
+//                 larger D runs in groups of 256 channels with the fragments reloaded).
 //   contraction : S_l[pt][q] = <f2_l(window point pt), f1(query q)> over D.  The window is
 //                 staged through LDS in 32-channel chunks (coalesced 16-byte loads of
 //                 128-byte records per pixel and chunk; bf16 mode loads only the hi half);
@@ -148,12 +149,31 @@ __device__ __forceinline__ void stage(const Stage<LVL, THREE>& st, int slot, uns
     }
 }
 
+// Query fragments of this wave for chunks g .. g+NCMAX-1: lane holds channels 8*(lane/16) .. +7 of
+// every chunk of query 16*wave + lane%16 (the B operand of the MFMA); empty slots hold zeros.
+template <bool THREE>
+__device__ __forceinline__ void load_queries(const BlockArgs& a, const ItemCtx& c, int g,
+                                             bf16x8 (&qhi)[NCMAX], bf16x8 (&qlo)[NCMAX]) {
+    const int pix = c.q_pix[c.wave * 16 + (c.lane & 15)];
+    const uint16_t* src = a.f1s + ((size_t)c.b * a.HW + max(pix, 0)) * 64 + (c.lane >> 4) * 8;
+#pragma unroll
+    for (int kk = 0; kk < NCMAX; ++kk) {
+        uint4 h = make_uint4(0, 0, 0, 0), l = make_uint4(0, 0, 0, 0);
+        if (g + kk < a.NC && pix >= 0) {
+            h = *reinterpret_cast<const uint4*>(src + (size_t)(g + kk) * a.f1_stride);
+            if (THREE) l = *reinterpret_cast<const uint4*>(src + (size_t)(g + kk) * a.f1_stride + 32);
+        }
+        qhi[kk] = __builtin_bit_cast(bf16x8, h);
+        qlo[kk] = __builtin_bit_cast(bf16x8, l);
+    }
+}
+
 // One level of one work item.  On entry `st` holds the staging plan and chunk 0 in ring slot 0
 // (fetched before the previous level's epilogue); before its own epilogue the pass plans the next
 // level and fetches its chunk 0 into `nx`, so that those loads fly under the tap writes.
-template <int LVL, bool THREE, class NextStage>
+template <int LVL, bool THREE, bool BIGD, class NextStage>
 __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
-                                           const bf16x8 (&qhi)[NCMAX], const bf16x8 (&qlo)[NCMAX],
+                                           bf16x8 (&qhi)[NCMAX], bf16x8 (&qlo)[NCMAX],
                                            Stage<LVL, THREE>& st, NextStage& nx) {
     using G = Geo<LVL, THREE>;
     constexpr int PD = G::PD;
@@ -190,21 +210,29 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
 
     // two LDS buffers: while the MFMAs read chunk kc from one, chunk kc+1 is written to the
     // other; one barrier per chunk.  Ring slot (k % PD) holds chunk k until it is staged.
+    // The wave holds query fragments for NCMAX chunks; a larger D runs in groups of NCMAX chunks,
+    // each with its own fragments and a restarted ring (BIGD; otherwise a single trip).
+    for (int g = 0; g < (BIGD ? a.NC : 1); g += NCMAX) {
+    const int nc = BIGD ? min(a.NC - g, NCMAX) : a.NC;
+    if (BIGD) {
+        if (g > 0 || LVL > 0) load_queries<THREE>(a, c, g, qhi, qlo);
+        if (g > 0) fetch<LVL, THREE>(a, st, 0, g);
+    }
 #pragma unroll
     for (int d = 1; d < PD; ++d)
-        if (d < a.NC) fetch<LVL, THREE>(a, st, d, d);
+        if (d < nc) fetch<LVL, THREE>(a, st, d, g + d);
     stage<LVL, THREE>(st, 0, smem, tid);
-    if (PD < a.NC) fetch<LVL, THREE>(a, st, 0, PD);
+    if (PD < nc) fetch<LVL, THREE>(a, st, 0, g + PD);
     __syncthreads();
 
 #pragma unroll
     for (int kc = 0; kc < NCMAX; ++kc) {
-        if (kc < a.NC) {                            // uniform
+        if (kc < nc) {                              // uniform
             const unsigned char* rows = smem + (kc & 1) * G::BUF_BYTES;
             unsigned char* other = smem + ((kc + 1) & 1) * G::BUF_BYTES;
-            if (PD > 1 && kc + 1 < a.NC) {          // the data is already here: stage first
+            if (PD > 1 && kc + 1 < nc) {          // the data is already here: stage first
                 stage<LVL, THREE>(st, (kc + 1) % PD, other, tid);
-                if (kc + 1 + PD < a.NC) fetch<LVL, THREE>(a, st, (kc + 1) % PD, kc + 1 + PD);
+                if (kc + 1 + PD < nc) fetch<LVL, THREE>(a, st, (kc + 1) % PD, g + kc + 1 + PD);
             }
             if (active) {
                 // window fragments are read two row blocks ahead of the MFMAs that use them
@@ -232,12 +260,13 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
                     __builtin_amdgcn_sched_group_barrier(0x008, THREE ? 3 : 1, 0);
                 }
             }
-            if (PD == 1 && kc + 1 < a.NC) {         // the loads had the MFMA phase to arrive
+            if (PD == 1 && kc + 1 < nc) {         // the loads had the MFMA phase to arrive
                 stage<LVL, THREE>(st, 0, other, tid);
-                if (kc + 2 < a.NC) fetch<LVL, THREE>(a, st, 0, kc + 2);
+                if (kc + 2 < nc) fetch<LVL, THREE>(a, st, 0, g + kc + 2);
             }
             __syncthreads();
         }
+    }
     }
     // the staging buffers are dead; S may overwrite them
     prefetch_next();
@@ -286,7 +315,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     __syncthreads();                            // S is dead
 }
 
-template <bool THREE>
+template <bool THREE, bool BIGD>
 __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     int* q_pix = reinterpret_cast<int*>(smem + UNION_BYTES);
@@ -327,41 +356,26 @@ __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     }
     __syncthreads();
 
-    // query fragments of this wave: lane holds channels 8*(lane/16) .. +7 of every chunk of
-    // query 16*wave + lane%16 (the B operand of the MFMA); empty slots hold zeros
     bf16x8 qhi[NCMAX], qlo[NCMAX];
-    {
-        const int pix = q_pix[c.wave * 16 + (c.lane & 15)];
-        const uint16_t* src = a.f1s + ((size_t)c.b * a.HW + max(pix, 0)) * 64 + (c.lane >> 4) * 8;
-#pragma unroll
-        for (int kc = 0; kc < NCMAX; ++kc) {
-            uint4 h = make_uint4(0, 0, 0, 0), l = make_uint4(0, 0, 0, 0);
-            if (kc < a.NC && pix >= 0) {
-                h = *reinterpret_cast<const uint4*>(src + (size_t)kc * a.f1_stride);
-                if (THREE) l = *reinterpret_cast<const uint4*>(src + (size_t)kc * a.f1_stride + 32);
-            }
-            qhi[kc] = __builtin_bit_cast(bf16x8, h);
-            qlo[kc] = __builtin_bit_cast(bf16x8, l);
-        }
-    }
+    load_queries<THREE>(a, c, 0, qhi, qlo);
 
     Stage<1, THREE> s1;
-    level_pass<0, THREE>(a, c, smem, qhi, qlo, s0, s1);
+    level_pass<0, THREE, BIGD>(a, c, smem, qhi, qlo, s0, s1);
     if (a.L > 1) {
         Stage<2, THREE> s2;
-        level_pass<1, THREE>(a, c, smem, qhi, qlo, s1, s2);
+        level_pass<1, THREE, BIGD>(a, c, smem, qhi, qlo, s1, s2);
         if (a.L > 2) {
             Stage<3, THREE> s3;
-            level_pass<2, THREE>(a, c, smem, qhi, qlo, s2, s3);
-            if (a.L > 3) level_pass<3, THREE>(a, c, smem, qhi, qlo, s3, s3);
+            level_pass<2, THREE, BIGD>(a, c, smem, qhi, qlo, s2, s3);
+            if (a.L > 3) level_pass<3, THREE, BIGD>(a, c, smem, qhi, qlo, s3, s3);
         }
     }
 }
 
-template <bool THREE>
+template <bool THREE, bool BIGD>
 hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStream_t s) {
     static bool attr_set = false;
-    auto kfn = block_kernel<THREE>;
+    auto kfn = block_kernel<THREE, BIGD>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -383,5 +397,7 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
 }  // namespace
 
 hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s) {
-    return prec == CORR_PREC_BF16 ? launch_items<false>(p, coords, out, s) : launch_items<true>(p, coords, out, s);
+    const bool big = p->D > CORR_BLOCK_MAX_D;
+    if (prec == CORR_PREC_BF16) return big ? launch_items<false, true>(p, coords, out, s) : launch_items<false, false>(p, coords, out, s);
+    return big ? launch_items<true, true>(p, coords, out, s) : launch_items<true, false>(p, coords, out, s);
 }

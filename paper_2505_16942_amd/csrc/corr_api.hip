@@ -231,7 +231,7 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec, const float* f
     switch (mode) {
         case CORR_MODE_BLOCK: {
             if (prec != CORR_PREC_BF16X3 && prec != CORR_PREC_BF16) return CORR_ERR_INVALID_ARG;
-            if (r != 4 || D > CORR_BLOCK_MAX_D) return CORR_ERR_UNSUPPORTED;
+            if (r != 4) return CORR_ERR_UNSUPPORTED;
             if (!(pyr->reps & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
             hipEvent_t* ev = nullptr;
             if (pyr->prof_on && pyr->prof_ev && pyr->prof_n < CORR_PROF_LOOKUPS)

@@ -8,7 +8,7 @@
 #define CORR_MAX_L 4
 #define CORR_CHUNK 32          // channels per chunk plane of the split representation
 #define CORR_GROUP 64          // queries per work item
-#define CORR_BLOCK_MAX_D 256   // the block kernel keeps a wave's query fragments for all D channels in registers
+#define CORR_BLOCK_MAX_D 256   // channels of query fragments a wave of the block kernel holds in registers at a time
 #define CORR_R 4               // radius the block kernels are built for
 #ifndef CORR_LOG_CX
 #define CORR_LOG_CX 3          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels

@@ -56,6 +56,8 @@ SMALL = [
     (1, 8, 8, 256, 4, 3.0),       # level 3 is a single pixel
     (1, 37, 53, 96, 2, 40.0),     # many windows partly or wholly outside
     (1, 19, 27, 224, 4, 5.0),     # seven channel chunks
+    (1, 18, 22, 288, 4, 5.0),     # more channels than a wave holds at a time: two groups (8 + 1 chunks)
+    (1, 12, 20, 1024, 3, 6.0),    # largest D: four full groups
 ]
 
 
@@ -158,13 +160,6 @@ def test_error_paths():
     with pytest.raises(b.CorrError) as e:
         b.corr_sample(f, pyr, c, r=3)
     assert e.value.status == b.CORR_ERR_UNSUPPORTED
-    pyr.destroy()
-    f = torch.zeros((1, 288, 16, 16), device=dev)           # block mode holds at most 256 channels per query
-    pyr = b.corr_pyramid_build(f, f, L=2, reps=3)
-    with pytest.raises(b.CorrError) as e:
-        b.corr_sample(f, pyr, c)
-    assert e.value.status == b.CORR_ERR_UNSUPPORTED
-    b.corr_sample(f, pyr, c, mode=b.CORR_MODE_ONDEMAND)
     pyr.destroy()
     # the 8K dense volume is reported, not run
     assert b.corr_full_volume_bytes(1, 540, 960, 4) == 1427549184000
