@@ -3,7 +3,7 @@
 // map that emits every pyramid level in the layouts the lookup kernels read.
 //
 // A workgroup owns 32 channels x (8 rows x 32 columns) of level 0.  The tile is
-// read once (128 B runs along x), pooled 2x2 in LDS level after level
+// read once (128 B runs along x; 16-byte loads when the rows allow it), pooled 2x2 in LDS level after level
 // (0.25f * (a + b + c + d), the order of the definition, in fp32) and written as
 //   split : [D/32][P][32 x bf16 hi | 32 x bf16 lo] with P = every pixel of every level and batch
 //           item (level-major, then batch, then row-major), so a 32-channel chunk of a window row
@@ -16,6 +16,13 @@
 namespace {
 
 constexpr int TILE_H = 8, TILE_W = 32, CH = CORR_CHUNK;
+
+// LDS tile index of (channel c, row, col): rows padded by one float, and every group of 8 channels
+// skewed by 16 floats so that the four 8-channel parts of one pixel fall in different banks
+template <int ROWS, int COLS>
+__device__ __forceinline__ int tix(int c, int row, int col) { return (c * ROWS + row) * (COLS + 1) + col + (c >> 3) * 16; }
+template <int ROWS, int COLS>
+constexpr int tile_floats() { return CH * ROWS * (COLS + 1) + (CH / 8 - 1) * 16; }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
     uint32_t u = __float_as_uint(x);
@@ -33,6 +40,7 @@ struct LevelOut {
 struct BuildArgs {
     const float* src;
     int B, D, H, W, nlev;
+    int vec4;          // rows can be read with aligned 16-byte loads (W % 4 == 0 and a 16-byte aligned base)
     LevelOut lv[CORR_MAX_L];
 };
 
@@ -40,7 +48,6 @@ struct BuildArgs {
 template <int ROWS, int COLS>
 __device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, int b, int kc, int D,
                                            int y0, int x0) {
-    constexpr int PITCH = COLS + 1;
     // one thread = one pixel x 8 channels (16 B of hi, 16 B of lo, 32 B of fp32)
     for (int w = threadIdx.x; w < ROWS * COLS * 4; w += blockDim.x) {
         const int part = w & 3, pix = w >> 2;
@@ -49,7 +56,7 @@ __device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, i
         if (y >= lo.H || x >= lo.W) continue;
         float v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = t[((part * 8 + k) * ROWS + row) * PITCH + col];
+        for (int k = 0; k < 8; ++k) v[k] = t[tix<ROWS, COLS>(part * 8 + k, row, col)];
         const size_t p = (size_t)y * lo.W + x;
         const size_t npix = (size_t)lo.H * lo.W;
         if (lo.split) {
@@ -78,25 +85,41 @@ __device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, i
 // dst[c][r][q] = 0.25f * (src[c][2r][2q] + src[c][2r][2q+1] + src[c][2r+1][2q] + src[c][2r+1][2q+1])
 template <int ROWS, int COLS>   // ROWS, COLS of the destination
 __device__ __forceinline__ void pool_level(const float* src, float* dst) {
-    constexpr int SP = 2 * COLS + 1, DP = COLS + 1;
+    constexpr int SP = 2 * COLS + 1;
     for (int w = threadIdx.x; w < CH * ROWS * COLS; w += blockDim.x) {
         const int c = w / (ROWS * COLS), rq = w % (ROWS * COLS);
         const int r = rq / COLS, q = rq % COLS;
-        const float* s = src + (c * (2 * ROWS) + 2 * r) * SP + 2 * q;
+        const float* s = src + tix<2 * ROWS, 2 * COLS>(c, 2 * r, 2 * q);
         const float a = s[0], bb = s[1], cc = s[SP], dd = s[SP + 1];
-        dst[(c * ROWS + r) * DP + q] = 0.25f * (((a + bb) + cc) + dd);
+        dst[tix<ROWS, COLS>(c, r, q)] = 0.25f * (((a + bb) + cc) + dd);
     }
 }
 
 __global__ __launch_bounds__(256) void build_features_kernel(BuildArgs a) {
-    __shared__ float t0[CH * TILE_H * (TILE_W + 1)];
-    __shared__ float t1[CH * (TILE_H / 2) * (TILE_W / 2 + 1)];
-    __shared__ float t2[CH * (TILE_H / 4) * (TILE_W / 4 + 1)];
-    __shared__ float t3[CH * (TILE_H / 8) * (TILE_W / 8 + 1)];
+    __shared__ float t0[tile_floats<TILE_H, TILE_W>()];
+    __shared__ float t1[tile_floats<TILE_H / 2, TILE_W / 2>()];
+    __shared__ float t2[tile_floats<TILE_H / 4, TILE_W / 4>()];
+    __shared__ float t3[tile_floats<TILE_H / 8, TILE_W / 8>()];
     const int NC = a.D / CH;
     const int b = blockIdx.z / NC, kc = blockIdx.z % NC;
     const int y0 = blockIdx.y * TILE_H, x0 = blockIdx.x * TILE_W;
-    {
+    if (a.vec4) {
+        // 16-byte loads: a wave reads the 8 rows x 128 B of one channel, the four waves four channels
+        const int col = (threadIdx.x & 7) * 4, row = (threadIdx.x >> 3) & 7, c0 = threadIdx.x >> 6;
+        const int y = y0 + row, x = x0 + col;
+        const bool ok = (y < a.H) && (x < a.W);              // a float4 is inside or outside as a whole
+        const float* src = a.src + (((size_t)b * a.D + kc * CH + c0) * a.H + (ok ? y : 0)) * a.W + (ok ? x : 0);
+        const size_t cstride = (size_t)a.H * a.W;
+        float4 v[CH / 4];
+#pragma unroll
+        for (int i = 0; i < CH / 4; ++i)
+            v[i] = ok ? *reinterpret_cast<const float4*>(src + (size_t)(4 * i) * cstride) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < CH / 4; ++i) {
+            float* d = t0 + tix<TILE_H, TILE_W>(c0 + 4 * i, row, col);
+            d[0] = v[i].x; d[1] = v[i].y; d[2] = v[i].z; d[3] = v[i].w;
+        }
+    } else {
         const int col = threadIdx.x % TILE_W, row = threadIdx.x / TILE_W;
         const int y = y0 + row, x = x0 + col;
         const bool ok = (y < a.H) && (x < a.W);
@@ -104,7 +127,7 @@ __global__ __launch_bounds__(256) void build_features_kernel(BuildArgs a) {
         const size_t cstride = (size_t)a.H * a.W;
 #pragma unroll 8
         for (int c = 0; c < CH; ++c)
-            t0[(c * TILE_H + row) * (TILE_W + 1) + col] = ok ? src[c * cstride] : 0.0f;
+            t0[tix<TILE_H, TILE_W>(c, row, col)] = ok ? src[c * cstride] : 0.0f;
     }
     __syncthreads();
     emit_level<TILE_H, TILE_W>(t0, a.lv[0], b, kc, a.D, y0, x0);
@@ -143,6 +166,7 @@ hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, 
                                  uint16_t* split, float* const* nhwc, hipStream_t s) {
     BuildArgs a;
     a.src = nchw; a.B = B; a.D = D; a.H = H; a.W = W; a.nlev = nlev;
+    a.vec4 = (W % 4 == 0) && (reinterpret_cast<uintptr_t>(nchw) % 16 == 0);
     size_t ptotal = 0;
     for (int l = 0; l < nlev; ++l) ptotal += (size_t)B * (H >> l) * (W >> l);
     size_t pbase = 0;

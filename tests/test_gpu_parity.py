@@ -72,6 +72,29 @@ def test_small_cases_all_modes(case, mode):
     _check(res, ref, FP32_TOL, "small %s mode %d" % (case, mode))
 
 
+def test_feature_maps_not_16_byte_aligned():
+    """W % 4 == 0 but the caller's maps start 4 bytes past a 16-byte boundary: the build must not
+    use aligned vector loads there."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 1, 16, 24, 64, 3
+    f1, f2, c = synth.small_case(41, B, H, W, D, flow_range=4.0)
+    ref = oracle.lookup(f1, f2, c, L=L, r=4)
+    n = f1.size
+    big1 = torch.empty(n + 4, dtype=torch.float32, device=dev)
+    big2 = torch.empty(n + 4, dtype=torch.float32, device=dev)
+    t1 = big1[1:1 + n].view(B, D, H, W)
+    t2 = big2[1:1 + n].view(B, D, H, W)
+    t1.copy_(torch.from_numpy(f1)); t2.copy_(torch.from_numpy(f2))
+    assert t1.data_ptr() % 16 == 4 and t1.is_contiguous()
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=3)
+    tc = torch.from_numpy(c).to(dev)
+    for mode in (b.CORR_MODE_BLOCK, b.CORR_MODE_ONDEMAND):
+        res = b.corr_sample(t1, pyr, tc, mode=mode)
+        _check(res.cpu().numpy(), ref, FP32_TOL, "unaligned maps mode %d" % mode)
+    pyr.destroy()
+
+
 @pytest.mark.parametrize("r", [1, 2, 3])
 @pytest.mark.parametrize("mode", [1, 2])
 def test_other_radii_reference_modes(r, mode):
