@@ -95,6 +95,47 @@ def test_feature_maps_not_16_byte_aligned():
     pyr.destroy()
 
 
+def test_lookups_replayed_from_a_hip_graph():
+    """corr_sample allocates nothing and clears its own counters with kernels, so a caller may
+    capture a sequence of lookups; every replay must equal the eager result."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 1, 30, 44, 64, 4
+    f1, f2, c0 = synth.small_case(51, B, H, W, D, flow_range=9.0)
+    _, _, c1 = synth.small_case(52, B, H, W, D, flow_range=9.0)
+    t1, t2 = torch.from_numpy(f1).to(dev), torch.from_numpy(f2).to(dev)
+    tcs = [torch.from_numpy(c0).to(dev), torch.from_numpy(c1).to(dev)]
+    outs = [torch.empty((B, L * 81, H, W), device=dev) for _ in range(2)]
+    pyr = b.corr_pyramid_build(t1, t2, L=L)
+
+    def job():
+        for t in range(2):
+            b.corr_sample(t1, pyr, tcs[t], out=outs[t])
+
+    job()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    _check(eager[0].cpu().numpy(), oracle.lookup(f1, f2, c0, L=L, r=4), FP32_TOL, "eager lookup 0")
+    _check(eager[1].cpu().numpy(), oracle.lookup(f1, f2, c1, L=L, r=4), FP32_TOL, "eager lookup 1")
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            job()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], eager[0]) and torch.equal(outs[1], eager[1]), "replay %d" % rep
+        b.corr_sample(t1, pyr, tcs[1], out=outs[0])          # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], eager[1])
+    pyr.destroy()
+
+
 @pytest.mark.parametrize("r", [1, 2, 3])
 @pytest.mark.parametrize("mode", [1, 2])
 def test_other_radii_reference_modes(r, mode):
