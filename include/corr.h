@@ -107,6 +107,19 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
                              int B, int H, int W, int D, int L, int r,
                              float* out, void* stream);
 
+/*
+ * Output layout option (not in the paper; its kernel writes the layout RAFT's next
+ * convolution reads, which is CORR_OUT_NCHW).  CORR_OUT_NHWC writes the same values as
+ * out[b, y, x, l*(2r+1)^2 + i*(2r+1) + j] (channels last: the L*(2r+1)^2 taps of a query are
+ * contiguous), which is what a channels-last convolution reads and what the block kernel
+ * can store in whole cache lines.  Everything else is as for corr_sample_mode, which is
+ * corr_sample_layout(mode, prec, CORR_OUT_NCHW, ...).
+ */
+typedef enum { CORR_OUT_NCHW = 0, CORR_OUT_NHWC = 1 } corr_out_layout;
+corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_layout layout,
+                               const float* fmap1, corr_pyramid* pyr, const float* coords,
+                               int B, int H, int W, int D, int L, int r, float* out, void* hip_stream);
+
 /* Exact size of the dense volume pyramid of Eq. 2: 4 * B * (H*W) * sum_l(H_l*W_l) bytes
  * (0 if a level is empty or L is out of range).  Pure host arithmetic. */
 size_t corr_full_volume_bytes(int B, int H, int W, int L);

@@ -18,11 +18,12 @@ CORR_OK = 0
 CORR_ERR_INVALID_ARG, CORR_ERR_UNSUPPORTED, CORR_ERR_OOM, CORR_ERR_HIP, CORR_ERR_MISSING_REP = -1, -2, -3, -4, -5
 CORR_MODE_BLOCK, CORR_MODE_ONDEMAND, CORR_MODE_FULLVOLUME = 0, 1, 2
 CORR_PREC_BF16X3, CORR_PREC_BF16 = 0, 1
+CORR_OUT_NCHW, CORR_OUT_NHWC = 0, 1
 CORR_REP_SPLIT, CORR_REP_F32 = 1, 2
 
 EXPORTS = [
     "corr_pyramid_build", "corr_pyramid_build_reps", "corr_pyramid_destroy", "corr_pyramid_bytes",
-    "corr_sample", "corr_sample_mode", "corr_full_volume_bytes", "corr_workspace_bytes",
+    "corr_sample", "corr_sample_mode", "corr_sample_layout", "corr_full_volume_bytes", "corr_workspace_bytes",
     "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry",
     "corr_copy_f32", "corr_status_string",
 ]
@@ -70,6 +71,8 @@ def load_library():
     lib.corr_sample.restype = ci
     lib.corr_sample_mode.argtypes = [ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
     lib.corr_sample_mode.restype = ci
+    lib.corr_sample_layout.argtypes = [ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
+    lib.corr_sample_layout.restype = ci
     lib.corr_full_volume_bytes.argtypes = [ci, ci, ci, ci]
     lib.corr_full_volume_bytes.restype = sz
     lib.corr_workspace_bytes.argtypes = [cu, ci, ci, ci, ci, ci]
@@ -161,21 +164,23 @@ def corr_pyramid_build(fmap1: torch.Tensor, fmap2: torch.Tensor, L: int = 4,
 
 def corr_sample(fmap1, pyramid: Pyramid, coords: torch.Tensor, r: int = 4,
                 out: torch.Tensor | None = None, mode: int = CORR_MODE_BLOCK,
-                prec: int = CORR_PREC_BF16X3) -> torch.Tensor:
-    """coords: [B, 2, H, W] fp32 on the GPU.  Returns out [B, L*(2r+1)^2, H, W] fp32."""
+                prec: int = CORR_PREC_BF16X3, layout: int = CORR_OUT_NCHW) -> torch.Tensor:
+    """coords: [B, 2, H, W] fp32 on the GPU.  Returns out fp32: [B, L*(2r+1)^2, H, W] for
+    CORR_OUT_NCHW, [B, H, W, L*(2r+1)^2] for CORR_OUT_NHWC."""
     lib = load_library()
     pc = _dev_f32(coords, "coords")
     B, H, W, D, L = pyramid.B, pyramid.H, pyramid.W, pyramid.D, pyramid.L
     if tuple(coords.shape) != (B, 2, H, W):
         raise ValueError("coords must be [B, 2, H, W] = %s" % ((B, 2, H, W),))
     K = 2 * r + 1
+    shape = (B, H, W, L * K * K) if layout == CORR_OUT_NHWC else (B, L * K * K, H, W)
     if out is None:
-        out = torch.empty((B, L * K * K, H, W), dtype=torch.float32, device=coords.device)
-    elif tuple(out.shape) != (B, L * K * K, H, W):
+        out = torch.empty(shape, dtype=torch.float32, device=coords.device)
+    elif tuple(out.shape) != shape:
         raise ValueError("out has the wrong shape")
     po = _dev_f32(out, "out")
     p1 = fmap1.data_ptr() if isinstance(fmap1, torch.Tensor) else None
-    st = lib.corr_sample_mode(mode, prec, p1, pyramid.handle, pc, B, H, W, D, L, r, po, _stream())
+    st = lib.corr_sample_layout(mode, prec, layout, p1, pyramid.handle, pc, B, H, W, D, L, r, po, _stream())
     if st != CORR_OK:
         raise CorrError(st, "corr_sample")
     return out

@@ -22,6 +22,7 @@ struct BinArgs {
     const float* coords;   // [B][2][H*W]
     float* out;            // [B][L*K*K][H*W]
     int B, HW, L;
+    int tap_stride, pix_stride;   // layout of out
     CellGrid g;
     int* bin_count;
     int* q_bin;
@@ -61,8 +62,8 @@ __global__ __launch_bounds__(256) void bin_count_kernel(BinArgs a) {
     a.q_bin[q] = bin;
     a.q_rank[q] = rank;
     if (bin < 0) {   // out of range at every level: the whole output column of this query is zero
-        float* o = a.out + (size_t)b * a.L * K * K * a.HW + p;
-        for (int t = 0; t < a.L * K * K; ++t) o[(size_t)t * a.HW] = 0.0f;
+        float* o = a.out + (size_t)b * a.L * K * K * a.HW + (size_t)p * a.pix_stride;
+        for (int t = 0; t < a.L * K * K; ++t) o[(size_t)t * a.tap_stride] = 0.0f;
     }
 }
 
@@ -209,6 +210,7 @@ hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipS
     const int HW = p->H * p->W, BN = p->B * HW;
     BinArgs a;
     a.coords = coords; a.out = out; a.B = p->B; a.HW = HW; a.L = p->L; a.g = p->grid;
+    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, p->grid.r);
     a.bin_count = p->bin_count; a.q_bin = p->q_bin; a.q_rank = p->q_rank;
     hipLaunchKernelGGL(bin_count_kernel, dim3((BN + 255) / 256), dim3(256), 0, s, a);
     hipError_t e = hipGetLastError();

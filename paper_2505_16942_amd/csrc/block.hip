@@ -46,6 +46,7 @@ struct BlockArgs {
     const int* n_items;
     float* out;
     int B, HW, NC, L;
+    int tap_stride, pix_stride;          // layout of out
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L], pix_base[CORR_MAX_L];
     int f1_stride, f2_stride;            // elements between chunk planes
     CellGrid g;
@@ -182,7 +183,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
     const int tid = c.tid, lane = c.lane, wave = c.wave;
-    float* o_lvl = a.out + ((size_t)(c.b * a.L + LVL) * KK) * a.HW;
+    float* o_lvl = a.out + (size_t)c.b * a.L * KK * a.HW + (size_t)(LVL * KK) * a.tap_stride;
     auto prefetch_next = [&]() {
         if constexpr (LVL + 1 < CORR_MAX_L) {
             if (LVL + 1 < a.L) { plan<LVL + 1, THREE>(a, c, nx); fetch<LVL + 1, THREE>(a, nx, 0, 0); }
@@ -193,8 +194,8 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     if (!touches) {             // uniform for the workgroup: this level's window is all padding
         prefetch_next();
         for (int q = lane; q < c.n; q += 64) {
-            float* o = o_lvl + c.q_pix[q];
-            for (int t = wave; t < KK; t += NW) o[(size_t)t * a.HW] = 0.f;
+            float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride;
+            for (int t = wave; t < KK; t += NW) o[(size_t)t * a.tap_stride] = 0.f;
         }
         return;
     }
@@ -292,7 +293,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
         const int i0 = wave == 0 ? 0 : 2 * wave + 1, i1 = 2 * wave + 3;   // 0..3, 3..5, 5..7, 7..9
         const float* s = S + (ry * G::WSX + rx + i0) * 64 + lane;
-        float* o = o_lvl + c.q_pix[q] + (size_t)(i0 * K) * a.HW;
+        float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride + (size_t)(i0 * K) * a.tap_stride;
         float left[K + 1], right[K + 1];
 #pragma unroll
         for (int j = 0; j <= K; ++j) left[j] = s[j * G::WSX * 64];
@@ -304,12 +305,12 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 const float hcur = left[j + 1] + fx * (right[j + 1] - left[j + 1]);
-                o[(size_t)j * a.HW] = hprev + fy * (hcur - hprev);
+                o[(size_t)j * a.tap_stride] = hprev + fy * (hcur - hprev);
                 hprev = hcur;
             }
 #pragma unroll
             for (int j = 0; j <= K; ++j) left[j] = right[j];
-            o += (size_t)K * a.HW;
+            o += (size_t)K * a.tap_stride;
         }
     }
     __syncthreads();                            // S is dead
@@ -385,6 +386,7 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
     BlockArgs a;
     a.f1s = p->f1_split; a.f2s = p->f2_split; a.coords = coords; a.perm = p->perm; a.items = p->items;
     a.n_items = p->n_items; a.out = out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L;
+    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, CORR_R);
     a.g = p->grid;
     for (int l = 0; l < CORR_MAX_L; ++l) { a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; a.pix_base[l] = p->f2_pix_base[l]; }
     a.f1_stride = p->B * p->H * p->W * 64; a.f2_stride = p->f2_pix_total * 64;

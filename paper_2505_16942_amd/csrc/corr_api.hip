@@ -220,14 +220,22 @@ corr_status corr_pyramid_destroy(corr_pyramid* pyr) {
 corr_status corr_sample_mode(corr_mode mode, corr_precision prec, const float* fmap1, corr_pyramid* pyr,
                              const float* coords, int B, int H, int W, int D, int L, int r,
                              float* out, void* stream) {
+    return corr_sample_layout(mode, prec, CORR_OUT_NCHW, fmap1, pyr, coords, B, H, W, D, L, r, out, stream);
+}
+
+corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_layout layout, const float* fmap1,
+                               corr_pyramid* pyr, const float* coords, int B, int H, int W, int D, int L, int r,
+                               float* out, void* stream) {
     (void)fmap1;
     if (!pyr || !coords || !out) return CORR_ERR_INVALID_ARG;
+    if (layout != CORR_OUT_NCHW && layout != CORR_OUT_NHWC) return CORR_ERR_INVALID_ARG;
     corr_status st = check_against(pyr, B, H, W, D, L);
     if (st != CORR_OK) return st;
     if (r < 1) return CORR_ERR_INVALID_ARG;
     if (r > 4) return CORR_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
+    pyr->out_nhwc = layout == CORR_OUT_NHWC;       // read by the launchers below
     switch (mode) {
         case CORR_MODE_BLOCK: {
             if (prec != CORR_PREC_BF16X3 && prec != CORR_PREC_BF16) return CORR_ERR_INVALID_ARG;

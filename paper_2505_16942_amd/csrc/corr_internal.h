@@ -73,6 +73,7 @@ struct corr_pyramid {
     float* vol[CORR_MAX_L];        // [B][H*W][H_l*W_l]
     int vol_valid;
     size_t bytes;
+    int out_nhwc;                  // layout of `out` for the call being enqueued (set by corr_sample_layout)
     // timing hook
     int prof_on, prof_n;
     hipEvent_t* prof_ev;           // [CORR_PROF_LOOKUPS][3]
@@ -92,6 +93,11 @@ static inline void corr_fill_grid(CellGrid* g, int H, int W, int L, int r) {
     g->tnx = (g->nbx + 7) >> 3;
     g->tny = (g->nby + 7) >> 3;
 }
+
+// Where tap t of pixel p of batch item b goes in `out`: b * taps * HW + t * tap_stride + p * pix_stride,
+// with (tap_stride, pix_stride) = (HW, 1) for NCHW and (1, taps) for NHWC.
+static inline int corr_tap_stride(const corr_pyramid* p) { return p->out_nhwc ? 1 : p->H * p->W; }
+static inline int corr_pix_stride(const corr_pyramid* p, int r) { return p->out_nhwc ? p->L * (2 * r + 1) * (2 * r + 1) : 1; }
 
 // launchers (each enqueues on `s` and returns hipGetLastError())
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,

@@ -59,6 +59,7 @@ struct FvArgs {
     const float* coords;
     float* out;
     int B, HW, L, r;
+    int tap_stride, pix_stride;      // layout of out
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
 };
 
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256) void vol_sample_kernel(FvArgs a) {
         v = (1.f - fx) * (1.f - fy) * vol_at(vp, H, W, y0, x0) + fx * (1.f - fy) * vol_at(vp, H, W, y0, x0 + 1)
           + (1.f - fx) * fy * vol_at(vp, H, W, y0 + 1, x0) + fx * fy * vol_at(vp, H, W, y0 + 1, x0 + 1);
     }
-    a.out[i] = v;
+    a.out[(size_t)b * a.L * KK * a.HW + (size_t)(l * KK + t) * a.tap_stride + (size_t)pix * a.pix_stride] = v;
 }
 
 }  // namespace
@@ -121,6 +122,7 @@ hipError_t launch_fullvol_sample(corr_pyramid* p, const float* coords, int r, fl
         a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
     }
     a.coords = coords; a.out = out; a.B = p->B; a.HW = p->H * p->W; a.L = p->L; a.r = r;
+    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, r);
     const int K = 2 * r + 1;
     const size_t total = (size_t)p->B * p->L * K * K * a.HW;
     hipLaunchKernelGGL(vol_sample_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);

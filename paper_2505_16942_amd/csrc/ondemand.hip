@@ -16,6 +16,7 @@ struct OdArgs {
     const float* coords;
     float* out;
     int B, HW, D, L, r;
+    int tap_stride, pix_stride;      // layout of out
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     float scale;
 };
@@ -43,7 +44,7 @@ __global__ __launch_bounds__(256) void ondemand_kernel(OdArgs a) {
     const bool finite_ok = (fabsf(cx0) <= CORR_COORD_LIMIT) && (fabsf(cy0) <= CORR_COORD_LIMIT);
     const int K = 2 * a.r + 1, Gs = K + 1, KK = K * K;
     for (int l = 0; l < a.L; ++l) {
-        float* o = a.out + ((size_t)(b * a.L + l) * KK) * a.HW + pix;
+        float* o = a.out + (size_t)b * a.L * KK * a.HW + (size_t)(l * KK) * a.tap_stride + (size_t)pix * a.pix_stride;
         const float inv = __uint_as_float((uint32_t)(127 - l) << 23);
         float fx = 0.f, fy = 0.f;
         int ox = 0, oy = 0;
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(256) void ondemand_kernel(OdArgs a) {
             live = (ox + K >= 0) && (ox <= a.Wl[l] - 1) && (oy + K >= 0) && (oy <= a.Hl[l] - 1);
         }
         if (!live) {
-            for (int t = lane; t < KK; t += 64) o[(size_t)t * a.HW] = 0.f;
+            for (int t = lane; t < KK; t += 64) o[(size_t)t * a.tap_stride] = 0.f;
             continue;
         }
         const float* f2b = a.f2[l] + (size_t)b * a.Hl[l] * a.Wl[l] * a.D;
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void ondemand_kernel(OdArgs a) {
         for (int t = lane; t < KK; t += 64) {
             const int i = t / K, j = t - i * K;   // i: x offset, j: y offset
             const float* s = S + j * Gs + i;
-            o[(size_t)t * a.HW] = w00 * s[0] + w01 * s[1] + w10 * s[Gs] + w11 * s[Gs + 1];
+            o[(size_t)t * a.tap_stride] = w00 * s[0] + w01 * s[1] + w10 * s[Gs] + w11 * s[Gs + 1];
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -100,6 +101,7 @@ hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* o
     OdArgs a;
     a.f1 = p->f1_nhwc; a.coords = coords; a.out = out;
     a.B = p->B; a.HW = p->H * p->W; a.D = p->D; a.L = p->L; a.r = r;
+    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, r);
     for (int l = 0; l < CORR_MAX_L; ++l) {
         a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr;
         a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];

@@ -95,6 +95,29 @@ def test_feature_maps_not_16_byte_aligned():
     pyr.destroy()
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_channels_last_output(mode):
+    """CORR_OUT_NHWC holds the same values as CORR_OUT_NCHW, taps contiguous per query; every
+    element is written (NaN prefill), null queries and untouched levels included."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 2, 21, 35, 64, 3
+    f1, f2, c = synth.small_case(61, B, H, W, D, flow_range=30.0)     # many windows partly or wholly outside
+    c[0, :, 3, 5] = np.float32(1e9)                                    # a null query
+    c[1, 0, 7, 9] = np.float32(np.nan)
+    ref_c = np.where(np.isfinite(c) & (np.abs(c) <= 2.0 ** 20), c, np.float32(-1e5))   # same taps: all zero
+    ref = oracle.lookup(f1, f2, ref_c, L=L, r=4)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=3)
+    out = torch.full((B, H, W, L * 81), float("nan"), dtype=torch.float32, device=dev)
+    b.corr_sample(t1, pyr, tc, out=out, mode=mode, layout=b.CORR_OUT_NHWC)
+    res = out.permute(0, 3, 1, 2).contiguous().cpu().numpy()
+    _check(res, ref, FP32_TOL, "channels-last mode %d" % mode)
+    nchw = b.corr_sample(t1, pyr, tc, mode=mode)
+    assert torch.equal(nchw, out.permute(0, 3, 1, 2)), "the two layouts hold different values"
+    pyr.destroy()
+
+
 def test_lookups_replayed_from_a_hip_graph():
     """corr_sample allocates nothing and clears its own counters with kernels, so a caller may
     capture a sequence of lookups; every replay must equal the eager result."""
