@@ -172,7 +172,7 @@ __device__ __forceinline__ void load_queries(const BlockArgs& a, const ItemCtx& 
 // One level of one work item.  On entry `st` holds the staging plan and chunk 0 in ring slot 0
 // (fetched before the previous level's epilogue); before its own epilogue the pass plans the next
 // level and fetches its chunk 0 into `nx`, so that those loads fly under the tap writes.
-template <int LVL, bool THREE, bool BIGD, class NextStage>
+template <int LVL, bool THREE, bool BIGD, bool NHWC, class NextStage>
 __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
                                            bf16x8 (&qhi)[NCMAX], bf16x8 (&qlo)[NCMAX],
                                            Stage<LVL, THREE>& st, NextStage& nx) {
@@ -183,7 +183,10 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
     const int tid = c.tid, lane = c.lane, wave = c.wave;
-    float* o_lvl = a.out + (size_t)c.b * a.L * KK * a.HW + (size_t)(LVL * KK) * a.tap_stride;
+    // channels-last output: the tap stride is the constant 1, so that the compiler can merge a
+    // query's consecutive taps into wide stores
+    const size_t tap_stride = NHWC ? 1 : (size_t)a.tap_stride;
+    float* o_lvl = a.out + (size_t)c.b * a.L * KK * a.HW + (size_t)(LVL * KK) * tap_stride;
     auto prefetch_next = [&]() {
         if constexpr (LVL + 1 < CORR_MAX_L) {
             if (LVL + 1 < a.L) { plan<LVL + 1, THREE>(a, c, nx); fetch<LVL + 1, THREE>(a, nx, 0, 0); }
@@ -195,7 +198,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         prefetch_next();
         for (int q = lane; q < c.n; q += 64) {
             float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride;
-            for (int t = wave; t < KK; t += NW) o[(size_t)t * a.tap_stride] = 0.f;
+            for (int t = wave; t < KK; t += NW) o[(size_t)t * tap_stride] = 0.f;
         }
         return;
     }
@@ -293,7 +296,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
         const int i0 = wave == 0 ? 0 : 2 * wave + 1, i1 = 2 * wave + 3;   // 0..3, 3..5, 5..7, 7..9
         const float* s = S + (ry * G::WSX + rx + i0) * 64 + lane;
-        float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride + (size_t)(i0 * K) * a.tap_stride;
+        float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride + (size_t)(i0 * K) * tap_stride;
         float left[K + 1], right[K + 1];
 #pragma unroll
         for (int j = 0; j <= K; ++j) left[j] = s[j * G::WSX * 64];
@@ -305,18 +308,18 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 const float hcur = left[j + 1] + fx * (right[j + 1] - left[j + 1]);
-                o[(size_t)j * a.tap_stride] = hprev + fy * (hcur - hprev);
+                o[(size_t)j * tap_stride] = hprev + fy * (hcur - hprev);
                 hprev = hcur;
             }
 #pragma unroll
             for (int j = 0; j <= K; ++j) left[j] = right[j];
-            o += (size_t)K * a.tap_stride;
+            o += (size_t)K * tap_stride;
         }
     }
     __syncthreads();                            // S is dead
 }
 
-template <bool THREE, bool BIGD>
+template <bool THREE, bool BIGD, bool NHWC>
 __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     int* q_pix = reinterpret_cast<int*>(smem + UNION_BYTES);
@@ -361,22 +364,22 @@ __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     load_queries<THREE>(a, c, 0, qhi, qlo);
 
     Stage<1, THREE> s1;
-    level_pass<0, THREE, BIGD>(a, c, smem, qhi, qlo, s0, s1);
+    level_pass<0, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s0, s1);
     if (a.L > 1) {
         Stage<2, THREE> s2;
-        level_pass<1, THREE, BIGD>(a, c, smem, qhi, qlo, s1, s2);
+        level_pass<1, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s1, s2);
         if (a.L > 2) {
             Stage<3, THREE> s3;
-            level_pass<2, THREE, BIGD>(a, c, smem, qhi, qlo, s2, s3);
-            if (a.L > 3) level_pass<3, THREE, BIGD>(a, c, smem, qhi, qlo, s3, s3);
+            level_pass<2, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s2, s3);
+            if (a.L > 3) level_pass<3, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s3, s3);
         }
     }
 }
 
-template <bool THREE, bool BIGD>
+template <bool THREE, bool BIGD, bool NHWC>
 hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStream_t s) {
     static bool attr_set = false;
-    auto kfn = block_kernel<THREE, BIGD>;
+    auto kfn = block_kernel<THREE, BIGD, NHWC>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -399,7 +402,10 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
 }  // namespace
 
 hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s) {
-    const bool big = p->D > CORR_BLOCK_MAX_D;
-    if (prec == CORR_PREC_BF16) return big ? launch_items<false, true>(p, coords, out, s) : launch_items<false, false>(p, coords, out, s);
-    return big ? launch_items<true, true>(p, coords, out, s) : launch_items<true, false>(p, coords, out, s);
+    const bool big = p->D > CORR_BLOCK_MAX_D, three = prec != CORR_PREC_BF16;
+#define CORR_LAUNCH(NHWC)                                                                                    \
+    (three ? (big ? launch_items<true, true, NHWC>(p, coords, out, s) : launch_items<true, false, NHWC>(p, coords, out, s))   \
+           : (big ? launch_items<false, true, NHWC>(p, coords, out, s) : launch_items<false, false, NHWC>(p, coords, out, s)))
+    return p->out_nhwc ? CORR_LAUNCH(true) : CORR_LAUNCH(false);
+#undef CORR_LAUNCH
 }
