@@ -30,6 +30,9 @@ def main() -> int:
     ap.add_argument("--config", default="8k", choices=["tiny", "1080p", "4k", "8k", "voronoi"])
     ap.add_argument("--lookups", type=int, default=12, help="corr_sample calls per pyramid build")
     ap.add_argument("--prec", default="bf16x3", choices=["bf16x3", "bf16"])
+    ap.add_argument("--out-layout", default="nchw", choices=["nchw", "nhwc"],
+                    help="layout of out: nchw is the headline (what the paper's kernel writes); nhwc is the "
+                         "library's channels-last option")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -61,6 +64,7 @@ def main() -> int:
     nl = args.lookups
     prec = cb.CORR_PREC_BF16X3 if args.prec == "bf16x3" else cb.CORR_PREC_BF16
     terms = 3 if args.prec == "bf16x3" else 1
+    layout = cb.CORR_OUT_NHWC if args.out_layout == "nhwc" else cb.CORR_OUT_NCHW
 
     t0 = time.time()
     f1, f2 = synth.features(cfg)
@@ -68,7 +72,8 @@ def main() -> int:
     gen_s = time.time() - t0
     t1, t2 = torch.from_numpy(f1).to(dev), torch.from_numpy(f2).to(dev)
     tcs = [torch.from_numpy(c).to(dev) for c in coords_h]
-    out = torch.empty((B, L * K * K, H, W), dtype=torch.float32, device=dev)
+    out = torch.empty((B, H, W, L * K * K) if layout == cb.CORR_OUT_NHWC else (B, L * K * K, H, W),
+                      dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     torch.cuda.reset_peak_memory_stats()
 
@@ -87,13 +92,13 @@ def main() -> int:
     def step():
         cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_SPLIT, pyramid=pyr)
         for tc in tcs:
-            cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec)
+            cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec, layout=layout)
 
     # untimed: per-lookup work counters of the binning pass (they depend on the coordinates)
     cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_SPLIT, pyramid=pyr)
     stats = []
     for tc in tcs:
-        cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec)
+        cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec, layout=layout)
         stats.append(cb.corr_last_block_stats(pyr))
     for _ in range(args.warmup):
         step()
@@ -122,7 +127,7 @@ def main() -> int:
     ev[1].record()
     for _ in range(reps_t):
         for tc in tcs:
-            cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec)
+            cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec, layout=layout)
     ev[2].record()
     torch.cuda.synchronize()
     build_ms = ev[0].elapsed_time(ev[1]) / reps_t
@@ -155,7 +160,7 @@ def main() -> int:
 
     # measured HBM traffic of the block kernel, if a counter summary for this workload is committed
     traffic_file = os.path.join(ROOT, "profiles", "block_kernel_%s_hbm_traffic.txt" % args.config)
-    if terms == 3 and os.path.exists(traffic_file):
+    if terms == 3 and args.out_layout == "nchw" and os.path.exists(traffic_file):
         for line in open(traffic_file):
             if line.startswith("traffic_bytes_per_launch:"):
                 roofline["traffic"] = float(line.split(":")[1])
@@ -168,7 +173,8 @@ def main() -> int:
         "dtype": "bf16x3->f32" if terms == 3 else "bf16->f32", "data": "synthetic",
         "config": {"workload": "%s: B=%d fmap [%d,%d,%d,%d] L=%d r=%d; step = 1 pyramid build + %d lookups"
                                % (args.config, B, B, D, H, W, L, r, nl),
-                   "seed": cfg["seed"], "lookups_per_build": nl, "lookups_per_call": lookups_per_call},
+                   "seed": cfg["seed"], "lookups_per_build": nl, "lookups_per_call": lookups_per_call,
+                   "out_layout": args.out_layout},
         "roofline": roofline,
         "breakdown_ms": {"pyramid_build": round(build_ms, 4), "one_lookup": round(lookup_ms, 4),
                          "binning_pass": round(bin_ms, 4),
@@ -189,11 +195,11 @@ def main() -> int:
         modes = {}
         for name, mode in (("ondemand", cb.CORR_MODE_ONDEMAND), ("fullvolume", cb.CORR_MODE_FULLVOLUME)):
             try:
-                cb.corr_sample(t1, pyr2, tcs[0], r=r, out=out, mode=mode)      # full volume: builds the volume
+                cb.corr_sample(t1, pyr2, tcs[0], r=r, out=out, mode=mode, layout=layout)      # full volume: builds the volume
                 torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                cb.corr_sample(t1, pyr2, tcs[0], r=r, out=out, mode=mode)
+                cb.corr_sample(t1, pyr2, tcs[0], r=r, out=out, mode=mode, layout=layout)
                 e1.record()
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1)
@@ -230,9 +236,10 @@ def main() -> int:
         tot_s = time.perf_counter() - tq
         work_s = max(tot_s - prep_s, 1e-6)
         # the same sample on the GPU result of lookup 0: parity of what was timed
-        cb.corr_sample(t1, pyr, tcs[0], r=r, out=out, prec=prec)
+        cb.corr_sample(t1, pyr, tcs[0], r=r, out=out, prec=prec, layout=layout)
         torch.cuda.synchronize()
-        got = out.reshape(-1)[torch.from_numpy(idx).to(dev)].cpu().numpy().astype(np.float64)
+        out_nchw = out.permute(0, 3, 1, 2) if layout == cb.CORR_OUT_NHWC else out     # indices are NCHW
+        got = out_nchw.reshape(-1)[torch.from_numpy(idx).to(dev)].cpu().numpy().astype(np.float64)
         maxc = float(np.abs(vals).max())
         result["cpu_baseline"] = {
             "value": idx.size / work_s, "unit": "lookups/s", "cores": corr_oracle.threads(), "kind": "oracle",
