@@ -107,6 +107,12 @@ def test_8k_every_output_and_full_volume_is_reported_not_run():
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
     del out2
+    # the channels-last layout holds the same values (the launch configuration bench.py --out-layout nhwc times)
+    out3 = torch.full((1, 540, 960, 324), float("nan"), dtype=torch.float32, device=out.device)
+    cb.corr_sample(t1, pyr, tc, out=out3, layout=cb.CORR_OUT_NHWC)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out3.permute(0, 3, 1, 2))
+    del out3
     # the dense volume would need 1.43 TB: the library says so instead of trying
     with pytest.raises(cb.CorrError) as e:
         cb.corr_sample(t1, pyr, tc, out=out, mode=cb.CORR_MODE_FULLVOLUME)
