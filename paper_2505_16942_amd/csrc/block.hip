@@ -33,7 +33,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int R = CORR_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 constexpr int NW = 4, NT = 64 * NW;
-constexpr int XCD_RUN = 128;
+constexpr int XCD_RUN = 64;   // about one 8x8 super-tile of cells
 constexpr int NCMAX = CORR_BLOCK_MAX_D / CORR_CHUNK;   // chunks of query fragments a wave can hold
 static_assert(CORR_GROUP == 64, "work items hold 64 queries: 16 per wave");
 
