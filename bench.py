@@ -65,6 +65,7 @@ def main() -> int:
     prec = cb.CORR_PREC_BF16X3 if args.prec == "bf16x3" else cb.CORR_PREC_BF16
     terms = 3 if args.prec == "bf16x3" else 1
     layout = cb.CORR_OUT_NHWC if args.out_layout == "nhwc" else cb.CORR_OUT_NCHW
+    rep = cb.CORR_REP_SPLIT if terms == 3 else cb.CORR_REP_BF16     # bf16 mode: hi parts alone, half the bytes
 
     t0 = time.time()
     f1, f2 = synth.features(cfg)
@@ -87,15 +88,15 @@ def main() -> int:
         torch.cuda.empty_cache()
         torch.cuda.reset_peak_memory_stats()
 
-    pyr = cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_SPLIT)
+    pyr = cb.corr_pyramid_build(t1, t2, L=L, reps=rep)
 
     def step():
-        cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_SPLIT, pyramid=pyr)
+        cb.corr_pyramid_build(t1, t2, L=L, reps=rep, pyramid=pyr)
         for tc in tcs:
             cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec, layout=layout)
 
     # untimed: per-lookup work counters of the binning pass (they depend on the coordinates)
-    cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_SPLIT, pyramid=pyr)
+    cb.corr_pyramid_build(t1, t2, L=L, reps=rep, pyramid=pyr)
     stats = []
     for tc in tcs:
         cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec, layout=layout)
@@ -123,7 +124,7 @@ def main() -> int:
     reps_t = 5
     ev[0].record()
     for _ in range(reps_t):
-        cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_SPLIT, pyramid=pyr)
+        cb.corr_pyramid_build(t1, t2, L=L, reps=rep, pyramid=pyr)
     ev[1].record()
     for _ in range(reps_t):
         for tc in tcs:

@@ -62,6 +62,9 @@ typedef enum {
 /* Feature representations a pyramid can hold (bit mask). */
 #define CORR_REP_SPLIT 1u   /* bf16 hi/lo, 32-channel chunk planes: read by CORR_MODE_BLOCK */
 #define CORR_REP_F32   2u   /* fp32 channels-last: read by CORR_MODE_ONDEMAND and CORR_MODE_FULLVOLUME */
+#define CORR_REP_BF16  4u   /* bf16 hi only, 32-channel chunk planes of 64-byte records: half the bytes of
+                               CORR_REP_SPLIT; read by CORR_MODE_BLOCK with CORR_PREC_BF16, which prefers it
+                               and otherwise reads the hi halves of CORR_REP_SPLIT */
 
 /*
  * Per image pair (paper: "Input Preprocessing"): re-lays fmap1 and builds levels 0..L-1 of fmap2
@@ -69,7 +72,9 @@ typedef enum {
  *   fmap1, fmap2 : device, dense fp32 [B, D, H, W] (NCHW); read only during the enqueued work.
  *   *pyr         : NULL -> a pyramid is allocated (hipMalloc; synchronous) and returned;
  *                  non-NULL -> must have been created with the same B,H,W,D,L and a superset of
- *                  `reps`; its buffers are reused and nothing is allocated.
+ *                  `reps`; its buffers are reused and nothing is allocated.  Representations not
+ *                  named in this call keep the previous pair and are not read by later lookups
+ *                  (those return CORR_ERR_MISSING_REP).
  *   reps         : mask of CORR_REP_*; corr_pyramid_build uses CORR_REP_SPLIT.
  * Limits: 1 <= L <= 4 with H >> (L-1) >= 1 and W >> (L-1) >= 1; D a multiple of 32, D <= 1024;
  * B*H*W*81*L < 2^31.  The library owns the pyramid; free it with corr_pyramid_destroy.

@@ -19,7 +19,7 @@ CORR_ERR_INVALID_ARG, CORR_ERR_UNSUPPORTED, CORR_ERR_OOM, CORR_ERR_HIP, CORR_ERR
 CORR_MODE_BLOCK, CORR_MODE_ONDEMAND, CORR_MODE_FULLVOLUME = 0, 1, 2
 CORR_PREC_BF16X3, CORR_PREC_BF16 = 0, 1
 CORR_OUT_NCHW, CORR_OUT_NHWC = 0, 1
-CORR_REP_SPLIT, CORR_REP_F32 = 1, 2
+CORR_REP_SPLIT, CORR_REP_F32, CORR_REP_BF16 = 1, 2, 4
 
 EXPORTS = [
     "corr_pyramid_build", "corr_pyramid_build_reps", "corr_pyramid_destroy", "corr_pyramid_bytes",

@@ -38,8 +38,8 @@ constexpr int NCMAX = CORR_BLOCK_MAX_D / CORR_CHUNK;   // chunks of query fragme
 static_assert(CORR_GROUP == 64, "work items hold 64 queries: 16 per wave");
 
 struct BlockArgs {
-    const uint16_t* f1s;                 // [NC][B*HW][64]
-    const uint16_t* f2s;                 // [NC][P][64], P = pixels of all levels; level l starts at pix_base[l]
+    const uint16_t* f1s;                 // [NC][B*HW][rec]
+    const uint16_t* f2s;                 // [NC][P][rec], P = pixels of all levels; level l starts at pix_base[l]
     const float* coords;                 // [B][2][HW]
     const int* perm;
     const int4* items;
@@ -49,6 +49,7 @@ struct BlockArgs {
     int tap_stride, pix_stride;          // layout of out
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L], pix_base[CORR_MAX_L];
     int f1_stride, f2_stride;            // elements between chunk planes
+    int rec;                             // elements per pixel record: 64 (hi + lo) or 32 (hi only)
     CellGrid g;
     float scale;
 };
@@ -112,6 +113,7 @@ template <int LVL, bool THREE>
 __device__ __forceinline__ void plan(const BlockArgs& a, const ItemCtx& c, Stage<LVL, THREE>& st) {
     using G = Geo<LVL, THREE>;
     const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
+    const int rec = THREE ? 64 : a.rec;
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
 #pragma unroll
@@ -122,7 +124,7 @@ __device__ __forceinline__ void plan(const BlockArgs& a, const ItemCtx& c, Stage
         if (row < G::NPTS) {
             const int wy = row / G::WSX, wx = row - wy * G::WSX;
             const int y = ys + wy, x = xs + wx;
-            if (y >= 0 && y < Hl && x >= 0 && x < Wl) off = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * 64;
+            if (y >= 0 && y < Hl && x >= 0 && x < Wl) off = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * rec;
         }
         st.goff[it] = off < 0 ? -1 : off + piece * 8;
     }
@@ -156,7 +158,7 @@ template <bool THREE>
 __device__ __forceinline__ void load_queries(const BlockArgs& a, const ItemCtx& c, int g,
                                              bf16x8 (&qhi)[NCMAX], bf16x8 (&qlo)[NCMAX]) {
     const int pix = c.q_pix[c.wave * 16 + (c.lane & 15)];
-    const uint16_t* src = a.f1s + ((size_t)c.b * a.HW + max(pix, 0)) * 64 + (c.lane >> 4) * 8;
+    const uint16_t* src = a.f1s + ((size_t)c.b * a.HW + max(pix, 0)) * (THREE ? 64 : a.rec) + (c.lane >> 4) * 8;
 #pragma unroll
     for (int kk = 0; kk < NCMAX; ++kk) {
         uint4 h = make_uint4(0, 0, 0, 0), l = make_uint4(0, 0, 0, 0);
@@ -392,7 +394,9 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
     a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, CORR_R);
     a.g = p->grid;
     for (int l = 0; l < CORR_MAX_L; ++l) { a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; a.pix_base[l] = p->f2_pix_base[l]; }
-    a.f1_stride = p->B * p->H * p->W * 64; a.f2_stride = p->f2_pix_total * 64;
+    a.rec = (!THREE && (p->built & CORR_REP_BF16)) ? 32 : 64;      // bf16 mode prefers the hi-only records
+    if (a.rec == 32) { a.f1s = p->f1_hi; a.f2s = p->f2_hi; }
+    a.f1_stride = p->B * p->H * p->W * a.rec; a.f2_stride = p->f2_pix_total * a.rec;
     a.scale = 1.0f / sqrtf((float)p->D);
     const int grid = (p->max_items + 8 * XCD_RUN - 1) / (8 * XCD_RUN) * (8 * XCD_RUN);
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), LDS_BYTES, s, a);

@@ -55,7 +55,7 @@ void free_all(corr_pyramid* p) {
     free_volume(p);
     (void)hipFree(p->f1_nhwc); (void)hipFree(p->f1_split);
     for (int l = 0; l < CORR_MAX_L; ++l) (void)hipFree(p->f2_nhwc[l]);
-    (void)hipFree(p->f2_split);
+    (void)hipFree(p->f2_split); (void)hipFree(p->f1_hi); (void)hipFree(p->f2_hi);
     (void)hipFree(p->bin_count); (void)hipFree(p->bin_off); (void)hipFree(p->q_bin); (void)hipFree(p->q_rank);
     if (p->prof_ev) {
         for (int i = 0; i < CORR_PROF_LOOKUPS * 3; ++i) (void)hipEventDestroy(p->prof_ev[i]);
@@ -71,6 +71,7 @@ size_t feature_bytes(unsigned reps, int B, int H, int W, int D, int L) {
     size_t per_px = 0;
     if (reps & CORR_REP_SPLIT) per_px += (size_t)D * 4;   // bf16 hi + lo
     if (reps & CORR_REP_F32) per_px += (size_t)D * 4;
+    if (reps & CORR_REP_BF16) per_px += (size_t)D * 2;
     return (size_t)B * px * per_px;
 }
 
@@ -88,12 +89,18 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
         for (int l = 0; l < L; ++l)
             need(dev_alloc(&p->f2_nhwc[l], (size_t)B * p->Hl[l] * p->Wl[l] * D, &p->bytes));
     }
-    if (reps & CORR_REP_SPLIT) {
-        need(dev_alloc(&p->f1_split, BN * D * 2, &p->bytes));
+    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16)) {      // what block mode reads, and its binning workspace
         size_t px = 0;
         for (int l = 0; l < L; ++l) { p->f2_pix_base[l] = (int)px; px += (size_t)B * p->Hl[l] * p->Wl[l]; }
         p->f2_pix_total = (int)px;
-        need(dev_alloc(&p->f2_split, px * D * 2, &p->bytes));
+        if (reps & CORR_REP_SPLIT) {
+            need(dev_alloc(&p->f1_split, BN * D * 2, &p->bytes));
+            need(dev_alloc(&p->f2_split, px * D * 2, &p->bytes));
+        }
+        if (reps & CORR_REP_BF16) {
+            need(dev_alloc(&p->f1_hi, BN * D, &p->bytes));
+            need(dev_alloc(&p->f2_hi, px * D, &p->bytes));
+        }
         need(dev_alloc(&p->bin_count, (size_t)p->nbins, &p->bytes));
         need(dev_alloc(&p->bin_off, (size_t)p->nbins, &p->bytes));
         need(dev_alloc(&p->q_bin, BN, &p->bytes));
@@ -146,7 +153,7 @@ size_t corr_full_volume_bytes(int B, int H, int W, int L) {
 size_t corr_workspace_bytes(unsigned reps, int B, int H, int W, int D, int L) {
     if (check_dims(B, H, W, D, L) != CORR_OK) return 0;
     size_t bytes = feature_bytes(reps, B, H, W, D, L);
-    if (reps & CORR_REP_SPLIT) {
+    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16)) {
         corr_pyramid tmp;
         memset(&tmp, 0, sizeof(tmp));
         tmp.B = B; tmp.H = H; tmp.W = W; tmp.D = D; tmp.L = L;
@@ -178,7 +185,7 @@ corr_status corr_bin_geometry(int H, int W, int L, int l, int* cell_x, int* cell
 corr_status corr_pyramid_build_reps(const float* fmap1, const float* fmap2, int B, int H, int W, int D, int L,
                                     unsigned reps, corr_pyramid** pyr, void* stream) {
     if (!fmap1 || !fmap2 || !pyr) return CORR_ERR_INVALID_ARG;
-    if (reps == 0 || (reps & ~(CORR_REP_SPLIT | CORR_REP_F32))) return CORR_ERR_INVALID_ARG;
+    if (reps == 0 || (reps & ~(CORR_REP_SPLIT | CORR_REP_F32 | CORR_REP_BF16))) return CORR_ERR_INVALID_ARG;
     corr_status st = check_dims(B, H, W, D, L);
     if (st != CORR_OK) return st;
     corr_pyramid* p = *pyr;
@@ -192,11 +199,14 @@ corr_status corr_pyramid_build_reps(const float* fmap1, const float* fmap2, int 
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     p->vol_valid = 0;     // a cached dense volume belongs to the previous pair
-    const bool sp = (reps & CORR_REP_SPLIT) != 0, fp = (reps & CORR_REP_F32) != 0;
+    p->built = reps;      // representations not rebuilt now still hold the previous pair
+    const bool sp = (reps & CORR_REP_SPLIT) != 0, fp = (reps & CORR_REP_F32) != 0, hi = (reps & CORR_REP_BF16) != 0;
     float* f1n[1] = {p->f1_nhwc};
-    hipError_t e = launch_build_features(fmap1, B, D, H, W, 1, sp ? p->f1_split : nullptr, fp ? f1n : nullptr, s);
+    hipError_t e = launch_build_features(fmap1, B, D, H, W, 1, sp ? p->f1_split : nullptr, hi ? p->f1_hi : nullptr,
+                                         fp ? f1n : nullptr, s);
     if (e == hipSuccess)
-        e = launch_build_features(fmap2, B, D, H, W, L, sp ? p->f2_split : nullptr, fp ? p->f2_nhwc : nullptr, s);
+        e = launch_build_features(fmap2, B, D, H, W, L, sp ? p->f2_split : nullptr, hi ? p->f2_hi : nullptr,
+                                  fp ? p->f2_nhwc : nullptr, s);
     if (e != hipSuccess) {
         if (!*pyr) free_all(p);
         return CORR_ERR_HIP;
@@ -240,7 +250,8 @@ corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_lay
         case CORR_MODE_BLOCK: {
             if (prec != CORR_PREC_BF16X3 && prec != CORR_PREC_BF16) return CORR_ERR_INVALID_ARG;
             if (r != 4) return CORR_ERR_UNSUPPORTED;
-            if (!(pyr->reps & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
+            if (!(pyr->built & (prec == CORR_PREC_BF16 ? (CORR_REP_SPLIT | CORR_REP_BF16) : CORR_REP_SPLIT)))
+                return CORR_ERR_MISSING_REP;
             hipEvent_t* ev = nullptr;
             if (pyr->prof_on && pyr->prof_ev && pyr->prof_n < CORR_PROF_LOOKUPS)
                 ev = pyr->prof_ev + (size_t)pyr->prof_n * 3;
@@ -253,12 +264,12 @@ corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_lay
             break;
         }
         case CORR_MODE_ONDEMAND: {
-            if (!(pyr->reps & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
+            if (!(pyr->built & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
             e = launch_ondemand(pyr, coords, r, out, s);
             break;
         }
         case CORR_MODE_FULLVOLUME: {
-            if (!(pyr->reps & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
+            if (!(pyr->built & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
             if (!pyr->vol_valid) {
                 if (!pyr->vol[0]) {
                     const size_t need = corr_full_volume_bytes(B, H, W, L);
@@ -289,7 +300,7 @@ corr_status corr_sample(const float* fmap1, corr_pyramid* pyr, const float* coor
 
 corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, void* stream) {
     if (!pyr || !stats) return CORR_ERR_INVALID_ARG;
-    if (!(pyr->reps & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
+    if (!(pyr->reps & (CORR_REP_SPLIT | CORR_REP_BF16))) return CORR_ERR_MISSING_REP;
     long long h[CORR_NSTATS];
     int hn[4];
     hipStream_t s = static_cast<hipStream_t>(stream);

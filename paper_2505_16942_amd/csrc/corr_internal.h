@@ -46,7 +46,8 @@ __host__ __device__ static inline void corr_cell_coords(const CellGrid& g, int i
 
 struct corr_pyramid {
     int B, H, W, D, L;
-    unsigned reps;
+    unsigned reps;                 // representations allocated
+    unsigned built;                // representations that hold the current pair (set by each build)
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     CellGrid grid;
     int nbins;                     // B * 64 * tnx * tny
@@ -58,6 +59,9 @@ struct corr_pyramid {
     // (f1: B*H*W; f2: every level, level-major then batch: pix_base[l] + b*H_l*W_l + y*W_l + x)
     uint16_t* f1_split;
     uint16_t* f2_split;
+    // CORR_REP_BF16: [D/32][P][32] bf16 (the hi parts alone), same pixel order
+    uint16_t* f1_hi;
+    uint16_t* f2_hi;
     int f2_pix_base[CORR_MAX_L];   // first pixel of level l in a chunk plane
     int f2_pix_total;              // pixels per chunk plane
     // block-mode workspace
@@ -101,7 +105,7 @@ static inline int corr_pix_stride(const corr_pyramid* p, int r) { return p->out_
 
 // launchers (each enqueues on `s` and returns hipGetLastError())
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
-                                 uint16_t* split, float* const* nhwc, hipStream_t s);
+                                 uint16_t* split, uint16_t* hi, float* const* nhwc, hipStream_t s);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s);
 hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipStream_t s);
 hipError_t launch_bin_stats(corr_pyramid* p, hipStream_t s);

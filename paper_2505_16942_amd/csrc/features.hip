@@ -8,6 +8,7 @@
 //   split : [D/32][P][32 x bf16 hi | 32 x bf16 lo] with P = every pixel of every level and batch
 //           item (level-major, then batch, then row-major), so a 32-channel chunk of a window row
 //           is one contiguous run and all levels share one chunk stride
+//   hi    : [D/32][P][32 x bf16]: the hi parts alone, same pixel order (bf16 mode reads half the bytes)
 //   nhwc  : [B][pixel][D] fp32
 // A level-l pixel is written iff it lies inside the floor-halved level size, so
 // a trailing odd row or column is dropped exactly as the definition says.
@@ -33,6 +34,7 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as
 
 struct LevelOut {
     uint16_t* split;   // may be null; base of the whole split buffer
+    uint16_t* hi;      // may be null; base of the whole hi-only buffer
     size_t ptotal, pbase;   // pixels per chunk plane, first pixel of this level in a plane
     float* nhwc;       // may be null
     int H, W;
@@ -59,6 +61,14 @@ __device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, i
         for (int k = 0; k < 8; ++k) v[k] = t[tix<ROWS, COLS>(part * 8 + k, row, col)];
         const size_t p = (size_t)y * lo.W + x;
         const size_t npix = (size_t)lo.H * lo.W;
+        if (lo.hi && !lo.split) {
+            uint32_t hi[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) hi[k] = f32_to_bf16_rne(v[k]);
+            uint16_t* dst = lo.hi + ((size_t)kc * lo.ptotal + lo.pbase + (size_t)b * npix + p) * CH + part * 8;
+            *reinterpret_cast<uint4*>(dst) = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16),
+                                                        hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+        }
         if (lo.split) {
             uint32_t hi[8], lw[8];
 #pragma unroll
@@ -73,6 +83,8 @@ __device__ __forceinline__ void emit_level(const float* t, const LevelOut& lo, i
                                   lw[4] | (lw[5] << 16), lw[6] | (lw[7] << 16));
             *reinterpret_cast<uint4*>(dst) = h4;
             *reinterpret_cast<uint4*>(dst + CH) = l4;
+            if (lo.hi)
+                *reinterpret_cast<uint4*>(lo.hi + ((size_t)kc * lo.ptotal + lo.pbase + (size_t)b * npix + p) * CH + part * 8) = h4;
         }
         if (lo.nhwc) {
             float* dst = lo.nhwc + ((size_t)b * npix + p) * D + kc * CH + part * 8;
@@ -163,7 +175,7 @@ hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s
 }
 
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
-                                 uint16_t* split, float* const* nhwc, hipStream_t s) {
+                                 uint16_t* split, uint16_t* hi, float* const* nhwc, hipStream_t s) {
     BuildArgs a;
     a.src = nchw; a.B = B; a.D = D; a.H = H; a.W = W; a.nlev = nlev;
     a.vec4 = (W % 4 == 0) && (reinterpret_cast<uintptr_t>(nchw) % 16 == 0);
@@ -172,6 +184,7 @@ hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, 
     size_t pbase = 0;
     for (int l = 0; l < CORR_MAX_L; ++l) {
         a.lv[l].split = l < nlev ? split : nullptr;
+        a.lv[l].hi = l < nlev ? hi : nullptr;
         a.lv[l].ptotal = ptotal; a.lv[l].pbase = pbase;
         if (l < nlev) pbase += (size_t)B * (H >> l) * (W >> l);
         a.lv[l].nhwc = (l < nlev && nhwc) ? nhwc[l] : nullptr;

@@ -95,6 +95,40 @@ def test_feature_maps_not_16_byte_aligned():
     pyr.destroy()
 
 
+def test_bf16_only_representation():
+    """CORR_REP_BF16 (hi parts alone, half the bytes) serves bf16 mode with the same bits as the hi
+    halves of CORR_REP_SPLIT; a representation that was not rebuilt for the current pair is refused."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 2, 26, 38, 96, 4
+    f1, f2, c = synth.small_case(71, B, H, W, D, flow_range=10.0)
+    ref = oracle.lookup(f1, f2, c, L=L, r=4)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    p_hi = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_BF16)
+    got_hi = b.corr_sample(t1, p_hi, tc, prec=b.CORR_PREC_BF16)
+    _check(got_hi.cpu().numpy(), ref, BF16_TOL, "bf16 mode on hi-only records")
+    with pytest.raises(b.CorrError) as e:
+        b.corr_sample(t1, p_hi, tc)                                   # bf16x3 needs the lo parts
+    assert e.value.status == b.CORR_ERR_MISSING_REP
+    assert p_hi.bytes() < b.corr_workspace_bytes(b.CORR_REP_SPLIT, B, H, W, D, L)
+    p_sp = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_SPLIT)
+    got_sp = b.corr_sample(t1, p_sp, tc, prec=b.CORR_PREC_BF16)
+    assert torch.equal(got_hi, got_sp)
+    p_hi.destroy(); p_sp.destroy()
+    # all three representations, then a rebuild of one of them only: the others are stale
+    p_all = b.corr_pyramid_build(t1, t2, L=L, reps=7)
+    _check(b.corr_sample(t1, p_all, tc).cpu().numpy(), ref, FP32_TOL, "bf16x3 with all representations")
+    assert torch.equal(b.corr_sample(t1, p_all, tc, prec=b.CORR_PREC_BF16), got_sp)
+    b.corr_pyramid_build(t2, t1, L=L, reps=b.CORR_REP_SPLIT, pyramid=p_all)      # another pair
+    with pytest.raises(b.CorrError) as e:
+        b.corr_sample(t2, p_all, tc, mode=b.CORR_MODE_ONDEMAND)
+    assert e.value.status == b.CORR_ERR_MISSING_REP
+    ref2 = oracle.lookup(f2, f1, c, L=L, r=4)
+    _check(b.corr_sample(t2, p_all, tc, prec=b.CORR_PREC_BF16).cpu().numpy(), ref2, BF16_TOL,
+           "bf16 mode after a split-only rebuild reads the split records")
+    p_all.destroy()
+
+
 @pytest.mark.parametrize("mode", [0, 1, 2])
 def test_channels_last_output(mode):
     """CORR_OUT_NHWC holds the same values as CORR_OUT_NCHW, taps contiguous per query; every
