@@ -144,8 +144,9 @@ def main() -> int:
     achieved_tf = flops / (blk_ms * 1e-3) / 1e12
     npyr = sum((H >> l) * (W >> l) for l in range(L))
     # algorithmic HBM bytes of one launch: fmap1 and every pyramid pixel once (bf16 hi+lo = 4 B per
-    # element), coords, the sorted query list, `out` once
-    bytes_alg = B * (N * D * 4 + npyr * D * 4 + N * 8 + N * 4 + N * L * K * K * 4)
+    # element; bf16 mode on hi-only records 2 B), coords, the sorted query list, `out` once
+    feat_b = 4 if terms == 3 else 2
+    bytes_alg = B * (N * D * feat_b + npyr * D * feat_b + N * 8 + N * 4 + N * L * K * K * 4)
     hbm_gbs = bytes_alg / (blk_ms * 1e-3) / 1e9
     roofline = {
         "bound": "mfma", "achieved": round(achieved_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

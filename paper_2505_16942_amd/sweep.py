@@ -53,7 +53,7 @@ def _run_point(width: int, iters: int, D: int, L: int = 4, r: int = 4, reps_time
     caller = (f1.numel() + f2.numel() + out.numel() + 2 * H * W) * 4
     res = {}
     modes = [("block", cb.CORR_MODE_BLOCK, cb.CORR_PREC_BF16X3, cb.CORR_REP_SPLIT),
-             ("block_bf16", cb.CORR_MODE_BLOCK, cb.CORR_PREC_BF16, cb.CORR_REP_SPLIT),
+             ("block_bf16", cb.CORR_MODE_BLOCK, cb.CORR_PREC_BF16, cb.CORR_REP_BF16),
              ("ondemand", cb.CORR_MODE_ONDEMAND, cb.CORR_PREC_BF16X3, cb.CORR_REP_F32),
              ("fullvolume", cb.CORR_MODE_FULLVOLUME, cb.CORR_PREC_BF16X3, cb.CORR_REP_F32)]
     for name, mode, prec, reps in modes:
