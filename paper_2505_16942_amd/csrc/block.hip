@@ -3,7 +3,7 @@
 // the computed block lives only in registers and LDS).
 //
 // One workgroup = one work item = (target cell, up to 64 of its queries), processed
-// level after level by four waves.  Wave w owns queries 16w .. 16w+15 of the item.
+// level after level by four waves (the two coarsest of four levels in one fused pass).  Wave w owns queries 16w .. 16w+15 of the item.
 //   queries     : each wave loads the bf16 hi (and lo) fragments of its 16 queries for all
 //                 D channels once per item, straight from global memory into the MFMA
 //                 B-operand layout, and keeps them in registers for all levels (D <= 256; a
@@ -81,8 +81,27 @@ struct Geo {
         return row * ROWB + ((piece ^ ((row / (16 / PPR)) & (PPR - 1))) << 4);
     }
 };
-constexpr int UNION_BYTES = cmax(cmax(Geo<0>::UNION_BYTES, Geo<1>::UNION_BYTES),
-                                 cmax(Geo<2>::UNION_BYTES, Geo<3>::UNION_BYTES));
+// A pass of the kernel covers level LVL, or (FUSE) levels LVL and LVL + 1 together: their
+// windows are staged one after the other as one block of rows, contracted in the same chunk loop
+// and sampled one after the other.  Fusing the two small coarse windows halves their share of
+// chunk steps, barriers and pipeline fills.
+template <int LVL, bool THREE = true, bool FUSE = false>
+struct Pass {
+    using A = Geo<LVL, THREE>;
+    using B = Geo<(LVL + 1 < CORR_MAX_L ? LVL + 1 : LVL), THREE>;
+    static constexpr int PPR = A::PPR, ROWB = A::ROWB;
+    static constexpr int ROWS = A::ROWS + (FUSE ? B::ROWS : 0);
+    static constexpr int NWB = ROWS / 16;
+    static constexpr int BUF_BYTES = ROWS * ROWB;         // one staged chunk
+    static constexpr int S_BYTES = ROWS * 64 * 4;
+    static constexpr int UNION_BYTES = cmax(2 * BUF_BYTES, S_BYTES);
+    static constexpr int ITERS = (ROWS * PPR + NT - 1) / NT;   // 16-byte pieces per thread and chunk
+    static constexpr int PD = FUSE ? 2 : A::PD;
+    static constexpr int NEXT = LVL + (FUSE ? 2 : 1);     // first level of the following pass
+};
+constexpr int UNION_BYTES = cmax(cmax(cmax(Geo<0>::UNION_BYTES, Geo<1>::UNION_BYTES),
+                                      cmax(Geo<2>::UNION_BYTES, Geo<3>::UNION_BYTES)),
+                                 Pass<2, true, true>::UNION_BYTES);
 constexpr int META_BYTES = CORR_GROUP * 12;
 constexpr int LDS_BYTES = UNION_BYTES + META_BYTES;
 
@@ -96,11 +115,11 @@ struct ItemCtx {
 
 // Per-thread staging state of one level: which 16-byte pieces of the window this thread
 // moves for every chunk, and a ring of PD chunks of them in registers.
-template <int LVL, bool THREE>
+template <int LVL, bool THREE, bool FUSE = false>
 struct Stage {
-    using G = Geo<LVL, THREE>;
-    int goff[G::ITERS];              // element offset into f2s at chunk 0, or -1 for a zero row
-    uint4 sv[G::PD][G::ITERS];
+    using P = Pass<LVL, THREE, FUSE>;
+    int goff[P::ITERS];              // element offset into f2s at chunk 0, or -1 for a zero row
+    uint4 sv[P::PD][P::ITERS];
 };
 
 template <int LVL>
@@ -109,46 +128,53 @@ __device__ __forceinline__ void window_origin(const ItemCtx& c, int& xs, int& ys
     ys = ((c.v << CORR_LOG_CY) >> LVL) - R;
 }
 
+// element offset (chunk 0) of window point `row` of level LVL of this item, or -1 for a zero row
 template <int LVL, bool THREE>
-__device__ __forceinline__ void plan(const BlockArgs& a, const ItemCtx& c, Stage<LVL, THREE>& st) {
+__device__ __forceinline__ int point_offset(const BlockArgs& a, const ItemCtx& c, int row) {
     using G = Geo<LVL, THREE>;
+    if (row >= G::NPTS) return -1;
     const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
-    const int rec = THREE ? 64 : a.rec;
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
+    const int wy = row / G::WSX, wx = row - wy * G::WSX;
+    const int y = ys + wy, x = xs + wx;
+    if (y < 0 || y >= Hl || x < 0 || x >= Wl) return -1;
+    return (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * (THREE ? 64 : a.rec);
+}
+
+template <int LVL, bool THREE, bool FUSE>
+__device__ __forceinline__ void plan(const BlockArgs& a, const ItemCtx& c, Stage<LVL, THREE, FUSE>& st) {
+    using P = Pass<LVL, THREE, FUSE>;
 #pragma unroll
-    for (int it = 0; it < G::ITERS; ++it) {
+    for (int it = 0; it < P::ITERS; ++it) {
         const int idx = it * NT + c.tid;
-        const int row = G::row_of(idx), piece = G::piece_of(idx);   // pieces 0..3: hi record, 4..7: lo record
-        int off = -1;
-        if (row < G::NPTS) {
-            const int wy = row / G::WSX, wx = row - wy * G::WSX;
-            const int y = ys + wy, x = xs + wx;
-            if (y >= 0 && y < Hl && x >= 0 && x < Wl) off = (a.pix_base[LVL] + (c.b * Hl + y) * Wl + x) * rec;
-        }
+        const int row = idx / P::PPR, piece = idx % P::PPR;         // pieces 0..3: hi record, 4..7: lo record
+        int off;
+        if (!FUSE || row < P::A::ROWS) off = point_offset<LVL, THREE>(a, c, row);
+        else off = point_offset<(FUSE ? LVL + 1 : LVL), THREE>(a, c, row - P::A::ROWS);
         st.goff[it] = off < 0 ? -1 : off + piece * 8;
     }
 }
 
 // global -> ring slot `slot` for chunk kc
-template <int LVL, bool THREE>
-__device__ __forceinline__ void fetch(const BlockArgs& a, Stage<LVL, THREE>& st, int slot, int kc) {
-    using G = Geo<LVL, THREE>;
+template <int LVL, bool THREE, bool FUSE>
+__device__ __forceinline__ void fetch(const BlockArgs& a, Stage<LVL, THREE, FUSE>& st, int slot, int kc) {
+    using P = Pass<LVL, THREE, FUSE>;
     const uint16_t* base = a.f2s + (size_t)kc * a.f2_stride;
 #pragma unroll
-    for (int it = 0; it < G::ITERS; ++it)
+    for (int it = 0; it < P::ITERS; ++it)
         st.sv[slot][it] = st.goff[it] >= 0 ? *reinterpret_cast<const uint4*>(base + st.goff[it]) : make_uint4(0, 0, 0, 0);
 }
 
 // ring slot -> LDS buffer
-template <int LVL, bool THREE>
-__device__ __forceinline__ void stage(const Stage<LVL, THREE>& st, int slot, unsigned char* buf, int tid) {
-    using G = Geo<LVL, THREE>;
+template <int LVL, bool THREE, bool FUSE>
+__device__ __forceinline__ void stage(const Stage<LVL, THREE, FUSE>& st, int slot, unsigned char* buf, int tid) {
+    using P = Pass<LVL, THREE, FUSE>;
 #pragma unroll
-    for (int it = 0; it < G::ITERS; ++it) {
+    for (int it = 0; it < P::ITERS; ++it) {
         const int idx = it * NT + tid;
-        if (G::row_of(idx) < G::ROWS)
-            *reinterpret_cast<uint4*>(buf + G::lds_off(G::row_of(idx), G::piece_of(idx))) = st.sv[slot][it];
+        if (idx / P::PPR < P::ROWS)
+            *reinterpret_cast<uint4*>(buf + P::A::lds_off(idx / P::PPR, idx % P::PPR)) = st.sv[slot][it];
     }
 }
 
@@ -171,125 +197,20 @@ __device__ __forceinline__ void load_queries(const BlockArgs& a, const ItemCtx& 
     }
 }
 
-// One level of one work item.  On entry `st` holds the staging plan and chunk 0 in ring slot 0
-// (fetched before the previous level's epilogue); before its own epilogue the pass plans the next
-// level and fetches its chunk 0 into `nx`, so that those loads fly under the tap writes.
-template <int LVL, bool THREE, bool BIGD, bool NHWC, class NextStage>
-__device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
-                                           bf16x8 (&qhi)[NCMAX], bf16x8 (&qlo)[NCMAX],
-                                           Stage<LVL, THREE>& st, NextStage& nx) {
+// The taps of level LVL for the item's queries, from that level's S rows in LDS ([point][query]).
+// lane = query; wave 0 takes tap columns (x offsets) 0..2, waves 1..3 two columns each.  A
+// footprint column is read from LDS once (all 2r+2 rows at once, so the reads overlap) and
+// serves as the right neighbour of one tap column and the left neighbour of the next.
+template <int LVL, bool THREE, bool NHWC>
+__device__ __forceinline__ void write_taps(const BlockArgs& a, const ItemCtx& c, const float* S) {
     using G = Geo<LVL, THREE>;
-    constexpr int PD = G::PD;
-    float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging buffers
-    const int Hl = a.Hl[LVL], Wl = a.Wl[LVL];
-    int xs, ys;
-    window_origin<LVL>(c, xs, ys);
-    const int tid = c.tid, lane = c.lane, wave = c.wave;
     // channels-last output: the tap stride is the constant 1, so that the compiler can merge a
     // query's consecutive taps into wide stores
     const size_t tap_stride = NHWC ? 1 : (size_t)a.tap_stride;
     float* o_lvl = a.out + (size_t)c.b * a.L * KK * a.HW + (size_t)(LVL * KK) * tap_stride;
-    auto prefetch_next = [&]() {
-        if constexpr (LVL + 1 < CORR_MAX_L) {
-            if (LVL + 1 < a.L) { plan<LVL + 1, THREE>(a, c, nx); fetch<LVL + 1, THREE>(a, nx, 0, 0); }
-        }
-    };
-
-    const bool touches = xs + G::WSX - 1 >= 0 && xs <= Wl - 1 && ys + G::WSY - 1 >= 0 && ys <= Hl - 1;
-    if (!touches) {             // uniform for the workgroup: this level's window is all padding
-        prefetch_next();
-        for (int q = lane; q < c.n; q += 64) {
-            float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride;
-            for (int t = wave; t < KK; t += NW) o[(size_t)t * tap_stride] = 0.f;
-        }
-        return;
-    }
-
-    f32x4 acc[G::NWB];
-#pragma unroll
-    for (int i = 0; i < G::NWB; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const bool active = wave * 16 < c.n;                     // this wave has queries
-    // fragment read: lane holds channels 8*(lane/16)..+7 of row wb*16 + lane%16
-    const int frag_hi = G::lds_off(lane & 15, lane >> 4);
-    const int frag_lo = G::lds_off(lane & 15, 4 + (lane >> 4));
-
-    // two LDS buffers: while the MFMAs read chunk kc from one, chunk kc+1 is written to the
-    // other; one barrier per chunk.  Ring slot (k % PD) holds chunk k until it is staged.
-    // The wave holds query fragments for NCMAX chunks; a larger D runs in groups of NCMAX chunks,
-    // each with its own fragments and a restarted ring (BIGD; otherwise a single trip).
-    for (int g = 0; g < (BIGD ? a.NC : 1); g += NCMAX) {
-    const int nc = BIGD ? min(a.NC - g, NCMAX) : a.NC;
-    if (BIGD) {
-        if (g > 0 || LVL > 0) load_queries<THREE>(a, c, g, qhi, qlo);
-        if (g > 0) fetch<LVL, THREE>(a, st, 0, g);
-    }
-#pragma unroll
-    for (int d = 1; d < PD; ++d)
-        if (d < nc) fetch<LVL, THREE>(a, st, d, g + d);
-    stage<LVL, THREE>(st, 0, smem, tid);
-    if (PD < nc) fetch<LVL, THREE>(a, st, 0, g + PD);
-    __syncthreads();
-
-#pragma unroll
-    for (int kc = 0; kc < NCMAX; ++kc) {
-        if (kc < nc) {                              // uniform
-            const unsigned char* rows = smem + (kc & 1) * G::BUF_BYTES;
-            unsigned char* other = smem + ((kc + 1) & 1) * G::BUF_BYTES;
-            if (PD > 1 && kc + 1 < nc) {          // the data is already here: stage first
-                stage<LVL, THREE>(st, (kc + 1) % PD, other, tid);
-                if (kc + 1 + PD < nc) fetch<LVL, THREE>(a, st, (kc + 1) % PD, g + kc + 1 + PD);
-            }
-            if (active) {
-                // window fragments are read two row blocks ahead of the MFMAs that use them
-                constexpr int PF = 2;
-                bf16x8 wh[G::NWB + PF], wl[G::NWB + PF];
-#pragma unroll
-                for (int wb = 0; wb < PF; ++wb) {
-                    wh[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * G::ROWB + frag_hi);
-                    if (THREE) wl[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * G::ROWB + frag_lo);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 * PF : PF, 0);
-#pragma unroll
-                for (int wb = 0; wb < G::NWB; ++wb) {
-                    if (wb + PF < G::NWB) {
-                        wh[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * G::ROWB + frag_hi);
-                        if (THREE) wl[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * G::ROWB + frag_lo);
-                    }
-                    if (THREE) {
-                        acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[wb], qhi[kc], acc[wb], 0, 0, 0);
-                        acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[wb], qlo[kc], acc[wb], 0, 0, 0);
-                    }
-                    acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[wb], qhi[kc], acc[wb], 0, 0, 0);
-                    // keep this order in the schedule: the reads for block wb + PF, then the MFMAs of block wb
-                    if (wb + PF < G::NWB) __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 : 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, THREE ? 3 : 1, 0);
-                }
-            }
-            if (PD == 1 && kc + 1 < nc) {         // the loads had the MFMA phase to arrive
-                stage<LVL, THREE>(st, 0, other, tid);
-                if (kc + 2 < nc) fetch<LVL, THREE>(a, st, 0, g + kc + 2);
-            }
-            __syncthreads();
-        }
-    }
-    }
-    // the staging buffers are dead; S may overwrite them
-    prefetch_next();
-
-    // lane holds query 16*wave + lane % 16, points 4*(lane/16)+v of every row block
-    if (active) {
-#pragma unroll
-        for (int wb = 0; wb < G::NWB; ++wb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                S[(wb * 16 + 4 * (lane >> 4) + v) * 64 + wave * 16 + (lane & 15)] = acc[wb][v] * a.scale;
-    }
-    __syncthreads();
-    // lane = query; wave 0 takes tap columns (x offsets) 0..2, waves 1..3 two columns each.  A
-    // footprint column is read from LDS once (all 2r+2 rows at once, so the reads overlap) and
-    // serves as the right neighbour of one tap column and the left neighbour of the next.
-    const int q = lane;
+    int xs, ys;
+    window_origin<LVL>(c, xs, ys);
+    const int q = c.lane, wave = c.wave;
     if (q < c.n) {
         const float inv = __uint_as_float((uint32_t)(127 - LVL) << 23);   // 2^-LVL
         const float cxl = c.q_cx[q] * inv, cyl = c.q_cy[q] * inv;
@@ -297,7 +218,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         const float fx = cxl - flx, fy = cyl - fly;
         const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
         const int i0 = wave == 0 ? 0 : 2 * wave + 1, i1 = 2 * wave + 3;   // 0..3, 3..5, 5..7, 7..9
-        const float* s = S + (ry * G::WSX + rx + i0) * 64 + lane;
+        const float* s = S + (ry * G::WSX + rx + i0) * 64 + q;
         float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride + (size_t)(i0 * K) * tap_stride;
         float left[K + 1], right[K + 1];
 #pragma unroll
@@ -318,6 +239,139 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
             o += (size_t)K * tap_stride;
         }
     }
+}
+
+// All taps of level LVL are zero for this item (its window is all padding).
+template <int LVL, bool NHWC>
+__device__ __forceinline__ void write_zero_taps(const BlockArgs& a, const ItemCtx& c) {
+    const size_t tap_stride = NHWC ? 1 : (size_t)a.tap_stride;
+    float* o_lvl = a.out + (size_t)c.b * a.L * KK * a.HW + (size_t)(LVL * KK) * tap_stride;
+    for (int q = c.lane; q < c.n; q += 64) {
+        float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride;
+        for (int t = c.wave; t < KK; t += NW) o[(size_t)t * tap_stride] = 0.f;
+    }
+}
+
+template <int LVL, bool THREE>
+__device__ __forceinline__ bool window_touches(const BlockArgs& a, const ItemCtx& c) {
+    using G = Geo<LVL, THREE>;
+    int xs, ys;
+    window_origin<LVL>(c, xs, ys);
+    return xs + G::WSX - 1 >= 0 && xs <= a.Wl[LVL] - 1 && ys + G::WSY - 1 >= 0 && ys <= a.Hl[LVL] - 1;
+}
+
+// One pass of one work item (one level, or two fused).  On entry `st` holds the staging plan and
+// chunk 0 in ring slot 0 (fetched before the previous pass's epilogue); before its own epilogue
+// the pass plans the next one and fetches its chunk 0 into `nx`, so that those loads fly under
+// the tap writes.
+template <int LVL, bool THREE, bool BIGD, bool NHWC, bool FUSE, class NextStage>
+__device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
+                                           bf16x8 (&qhi)[NCMAX], bf16x8 (&qlo)[NCMAX],
+                                           Stage<LVL, THREE, FUSE>& st, NextStage& nx) {
+    using P = Pass<LVL, THREE, FUSE>;
+    using G = typename P::A;
+    constexpr int PD = P::PD;
+    constexpr int LVL2 = FUSE ? LVL + 1 : LVL;               // the second level of a fused pass
+    float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the staging buffers
+    const int tid = c.tid, lane = c.lane, wave = c.wave;
+    auto prefetch_next = [&]() {
+        if constexpr (P::NEXT < CORR_MAX_L) {
+            if (P::NEXT < a.L) { plan(a, c, nx); fetch(a, nx, 0, 0); }
+        }
+    };
+
+    // uniform for the workgroup: a window that is all padding gives zero taps
+    const bool touches = window_touches<LVL, THREE>(a, c) || (FUSE && window_touches<LVL2, THREE>(a, c));
+    if (!touches) {
+        prefetch_next();
+        write_zero_taps<LVL, NHWC>(a, c);
+        if (FUSE) write_zero_taps<LVL2, NHWC>(a, c);
+        return;
+    }
+
+    f32x4 acc[P::NWB];
+#pragma unroll
+    for (int i = 0; i < P::NWB; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const bool active = wave * 16 < c.n;                     // this wave has queries
+    // fragment read: lane holds channels 8*(lane/16)..+7 of row wb*16 + lane%16
+    const int frag_hi = G::lds_off(lane & 15, lane >> 4);
+    const int frag_lo = G::lds_off(lane & 15, 4 + (lane >> 4));
+
+    // two LDS buffers: while the MFMAs read chunk kc from one, chunk kc+1 is written to the
+    // other; one barrier per chunk.  Ring slot (k % PD) holds chunk k until it is staged.
+    // The wave holds query fragments for NCMAX chunks; a larger D runs in groups of NCMAX chunks,
+    // each with its own fragments and a restarted ring (BIGD; otherwise a single trip).
+    for (int g = 0; g < (BIGD ? a.NC : 1); g += NCMAX) {
+    const int nc = BIGD ? min(a.NC - g, NCMAX) : a.NC;
+    if (BIGD) {
+        if (g > 0 || LVL > 0) load_queries<THREE>(a, c, g, qhi, qlo);
+        if (g > 0) fetch(a, st, 0, g);
+    }
+#pragma unroll
+    for (int d = 1; d < PD; ++d)
+        if (d < nc) fetch(a, st, d, g + d);
+    stage(st, 0, smem, tid);
+    if (PD < nc) fetch(a, st, 0, g + PD);
+    __syncthreads();
+
+#pragma unroll
+    for (int kc = 0; kc < NCMAX; ++kc) {
+        if (kc < nc) {                              // uniform
+            const unsigned char* rows = smem + (kc & 1) * P::BUF_BYTES;
+            unsigned char* other = smem + ((kc + 1) & 1) * P::BUF_BYTES;
+            if (PD > 1 && kc + 1 < nc) {            // the data is already here: stage first
+                stage(st, (kc + 1) % PD, other, tid);
+                if (kc + 1 + PD < nc) fetch(a, st, (kc + 1) % PD, g + kc + 1 + PD);
+            }
+            if (active) {
+                // window fragments are read two row blocks ahead of the MFMAs that use them
+                constexpr int PF = 2;
+                bf16x8 wh[P::NWB + PF], wl[P::NWB + PF];
+#pragma unroll
+                for (int wb = 0; wb < PF; ++wb) {
+                    wh[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * G::ROWB + frag_hi);
+                    if (THREE) wl[wb] = *reinterpret_cast<const bf16x8*>(rows + wb * 16 * G::ROWB + frag_lo);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 * PF : PF, 0);
+#pragma unroll
+                for (int wb = 0; wb < P::NWB; ++wb) {
+                    if (wb + PF < P::NWB) {
+                        wh[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * G::ROWB + frag_hi);
+                        if (THREE) wl[wb + PF] = *reinterpret_cast<const bf16x8*>(rows + (wb + PF) * 16 * G::ROWB + frag_lo);
+                    }
+                    if (THREE) {
+                        acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[wb], qhi[kc], acc[wb], 0, 0, 0);
+                        acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[wb], qlo[kc], acc[wb], 0, 0, 0);
+                    }
+                    acc[wb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[wb], qhi[kc], acc[wb], 0, 0, 0);
+                    // keep this order in the schedule: the reads for block wb + PF, then the MFMAs of block wb
+                    if (wb + PF < P::NWB) __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 : 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, THREE ? 3 : 1, 0);
+                }
+            }
+            if (PD == 1 && kc + 1 < nc) {         // the loads had the MFMA phase to arrive
+                stage(st, 0, other, tid);
+                if (kc + 2 < nc) fetch(a, st, 0, g + kc + 2);
+            }
+            __syncthreads();
+        }
+    }
+    }
+    // the staging buffers are dead; S may overwrite them
+    prefetch_next();
+
+    // lane holds query 16*wave + lane % 16, points 4*(lane/16)+v of every row block
+    if (active) {
+#pragma unroll
+        for (int wb = 0; wb < P::NWB; ++wb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                S[(wb * 16 + 4 * (lane >> 4) + v) * 64 + wave * 16 + (lane & 15)] = acc[wb][v] * a.scale;
+    }
+    __syncthreads();
+    write_taps<LVL, THREE, NHWC>(a, c, S);
+    if (FUSE) write_taps<LVL2, THREE, NHWC>(a, c, S + G::ROWS * 64);
     __syncthreads();                            // S is dead
 }
 
@@ -347,8 +401,8 @@ __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
 
     // level 0's first chunk starts to move before anything else
     Stage<0, THREE> s0;
-    plan<0, THREE>(a, c, s0);
-    fetch<0, THREE>(a, s0, 0, 0);
+    plan(a, c, s0);
+    fetch(a, s0, 0, 0);
 
     if (c.tid < CORR_GROUP) {
         int pix = -1;
@@ -365,16 +419,17 @@ __global__ __launch_bounds__(NT, 2) void block_kernel(BlockArgs a) {
     bf16x8 qhi[NCMAX], qlo[NCMAX];
     load_queries<THREE>(a, c, 0, qhi, qlo);
 
+    // passes: level 0, level 1, then levels 2 and 3 together when there are four
     Stage<1, THREE> s1;
-    level_pass<0, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s0, s1);
-    if (a.L > 1) {
+    level_pass<0, THREE, BIGD, NHWC, false>(a, c, smem, qhi, qlo, s0, s1);
+    if (a.L == 4) {
+        Stage<2, THREE, true> s23;
+        level_pass<1, THREE, BIGD, NHWC, false>(a, c, smem, qhi, qlo, s1, s23);
+        level_pass<2, THREE, BIGD, NHWC, true>(a, c, smem, qhi, qlo, s23, s23);
+    } else if (a.L > 1) {
         Stage<2, THREE> s2;
-        level_pass<1, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s1, s2);
-        if (a.L > 2) {
-            Stage<3, THREE> s3;
-            level_pass<2, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s2, s3);
-            if (a.L > 3) level_pass<3, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, s3, s3);
-        }
+        level_pass<1, THREE, BIGD, NHWC, false>(a, c, smem, qhi, qlo, s1, s2);
+        if (a.L > 2) level_pass<2, THREE, BIGD, NHWC, false>(a, c, smem, qhi, qlo, s2, s2);
     }
 }
 
