@@ -95,6 +95,18 @@ def test_feature_maps_not_16_byte_aligned():
     pyr.destroy()
 
 
+@pytest.mark.parametrize("reps", [1, 2, 3, 4, 5, 7])
+def test_pyramid_bytes_equal_the_host_estimate(reps):
+    """corr_workspace_bytes (host arithmetic) is what a pyramid with those representations holds."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 2, 37, 53, 96, 3
+    f = torch.zeros((B, D, H, W), device=dev)
+    pyr = b.corr_pyramid_build(f, f, L=L, reps=reps)
+    assert pyr.bytes() == b.corr_workspace_bytes(reps, B, H, W, D, L)
+    pyr.destroy()
+
+
 def test_bf16_only_representation():
     """CORR_REP_BF16 (hi parts alone, half the bytes) serves bf16 mode with the same bits as the hi
     halves of CORR_REP_SPLIT; a representation that was not rebuilt for the current pair is refused."""
