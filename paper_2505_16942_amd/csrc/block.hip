@@ -234,7 +234,7 @@ __device__ __forceinline__ void write_taps(const BlockArgs& a, const ItemCtx& c,
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 const float hcur = left[j + 1] + fx * (right[j + 1] - left[j + 1]);
-                o[(size_t)j * tap_stride] = hprev + fy * (hcur - hprev);
+                o[(size_t)j * tap_stride] = (hprev + fy * (hcur - hprev)) * a.scale;    // 1/sqrt(D), once per tap
                 hprev = hcur;
             }
 #pragma unroll
@@ -370,7 +370,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         for (int wb = 0; wb < P::NWB; ++wb)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                S[(wb * 16 + 4 * (lane >> 4) + v) * 64 + wave * 16 + (lane & 15)] = acc[wb][v] * a.scale;
+                S[(wb * 16 + 4 * (lane >> 4) + v) * 64 + wave * 16 + (lane & 15)] = acc[wb][v];
     }
     __syncthreads();
     write_taps<LVL, THREE, NHWC>(a, c, S);
