@@ -183,7 +183,8 @@ __device__ __forceinline__ void stage(const Stage<LVL, THREE, FUSE>& st, int slo
 #pragma unroll
     for (int it = 0; it < P::ITERS; ++it) {
         const int idx = it * NT + tid;
-        if (idx / P::PPR < P::ROWS)
+        // only the last iteration can run past the staged rows
+        if ((it + 1) * NT <= P::ROWS * P::PPR || idx / P::PPR < P::ROWS)
             *reinterpret_cast<uint4*>(buf + P::A::lds_off(idx / P::PPR, idx % P::PPR)) = st.sv[slot][it];
     }
 }
