@@ -16,6 +16,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "corr_oracle.c")
 _LIB = os.path.join(_HERE, "libcorr_oracle.so")
 _lib = None
+# The mutation test loads deliberately broken builds of the oracle through this variable to show
+# that the pins reject them; nothing else sets it.
+_OVERRIDE = os.environ.get("CORR_ORACLE_LIB_OVERRIDE")
 
 
 def build(force: bool = False) -> str:
@@ -31,8 +34,11 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        if _OVERRIDE:
+            lib = ctypes.CDLL(_OVERRIDE)
+        else:
+            build()
+            lib = ctypes.CDLL(_LIB)
         f32p = np.ctypeslib.ndpointer(np.float32, flags="C_CONTIGUOUS")
         f64p = np.ctypeslib.ndpointer(np.float64, flags="C_CONTIGUOUS")
         i64p = np.ctypeslib.ndpointer(np.int64, flags="C_CONTIGUOUS")
