@@ -97,7 +97,7 @@ size_t corr_pyramid_bytes(const corr_pyramid* pyr);
  *   pyr     : pyramid built for the same B,H,W,D,L.
  *   coords  : device fp32 [B, 2, H, W]; channel 0 = x, 1 = y, absolute target position in
  *             level-0 pixels of fmap2.
- *   r       : lookup radius; block mode is built for r = 4, the other modes for 1 <= r <= 4.
+ *   r       : lookup radius; 1 <= r <= 4 in every mode.
  *   out     : device fp32 [B, L*(2r+1)^2, H, W], fully overwritten (no need to zero it).
  * Allocates nothing, except CORR_MODE_FULLVOLUME on its first call for a pyramid build (the dense
  * volume, cached in the pyramid until the next build or destroy).  Work is enqueued on `stream`;

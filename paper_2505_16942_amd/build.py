@@ -11,16 +11,20 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libcorr_mi355x.so")
 OBJ_DIR = os.path.join(PKG, "_build")
-SOURCES = ["corr_api.hip", "features.hip", "binning.hip", "block.hip", "ondemand.hip", "fullvol.hip"]
+# (source, object name, extra flags); block.hip is built once per lookup radius
+SOURCES = [("corr_api.hip", "corr_api.o", []), ("features.hip", "features.o", []), ("binning.hip", "binning.o", []),
+           ("ondemand.hip", "ondemand.o", []), ("fullvol.hip", "fullvol.o", [])]
+SOURCES += [("block.hip", "block_r%d.o" % r, ["-DCORR_BLOCK_R=%d" % r]) for r in (4, 3, 2, 1)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + INCLUDE, "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 FLAGS += os.environ.get("CORR_EXTRA_HIPCC_FLAGS", "").split()   # for experiments only
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(job) -> str:
+    src, objname, extra = job
+    obj = os.path.join(OBJ_DIR, objname)
+    cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

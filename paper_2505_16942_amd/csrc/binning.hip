@@ -21,7 +21,7 @@ namespace {
 struct BinArgs {
     const float* coords;   // [B][2][H*W]
     float* out;            // [B][L*K*K][H*W]
-    int B, HW, L;
+    int B, HW, L, r;              // r: radius of this lookup (the grid is laid out for the largest)
     int tap_stride, pix_stride;   // layout of out
     CellGrid g;
     int* bin_count;
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void bin_count_kernel(BinArgs a) {
     const int b = real ? q / a.HW : 0, p = real ? q - b * a.HW : 0;
     const float cx = real ? a.coords[((size_t)b * 2 + 0) * a.HW + p] : NAN;
     const float cy = real ? a.coords[((size_t)b * 2 + 1) * a.HW + p] : NAN;
-    const int K = 2 * a.g.r + 1;
+    const int K = 2 * a.r + 1;
     // comparisons are false for NaN, so non-finite coordinates are "not ok"
     const bool finite_ok = (fabsf(cx) <= CORR_COORD_LIMIT) && (fabsf(cy) <= CORR_COORD_LIMIT);
     int bin = -1;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void bin_count_kernel(BinArgs a) {
 }
 
 struct ScanArgs {
-    int nbins, L, BN;
+    int nbins, L, BN, r;
     CellGrid g;
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     int* bin_count;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(1024) void bin_scan_kernel(ScanArgs a) {
 __global__ __launch_bounds__(256) void bin_stats_kernel(ScanArgs a) {
     const int g = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & 63;
-    const int K = 2 * a.g.r + 1;
+    const int K = 2 * a.r + 1;
     long long v[CORR_MAX_L][4] = {};
     if (g < a.nbins) {
         const int end = g + 1 < a.nbins ? a.bin_off[g + 1] : a.n_items[1];
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void bin_stats_kernel(ScanArgs a) {
                 if (l >= a.L) break;
                 // window of this cell at level l and whether it touches the level at all
                 const int wsx = max((1 << a.g.log_cx) >> l, 1) + K, wsy = max((1 << a.g.log_cy) >> l, 1) + K;
-                const int xs = ((u << a.g.log_cx) >> l) - a.g.r, ys = ((w << a.g.log_cy) >> l) - a.g.r;
+                const int xs = ((u << a.g.log_cx) >> l) - a.r, ys = ((w << a.g.log_cy) >> l) - a.r;
                 if (xs + wsx - 1 >= 0 && xs <= a.Wl[l] - 1 && ys + wsy - 1 >= 0 && ys <= a.Hl[l] - 1) {
                     v[l][0] = items_here; v[l][1] = (long long)wsx * wsy * pad_q;
                     v[l][2] = (long long)wsx * wsy * c; v[l][3] = c;
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(const int* __restrict_
 
 static ScanArgs scan_args(corr_pyramid* p) {
     ScanArgs sc;
-    sc.nbins = p->nbins; sc.L = p->L; sc.BN = p->B * p->H * p->W; sc.g = p->grid;
+    sc.nbins = p->nbins; sc.L = p->L; sc.BN = p->B * p->H * p->W; sc.g = p->grid; sc.r = p->last_r;
     for (int l = 0; l < CORR_MAX_L; ++l) { sc.Hl[l] = p->Hl[l]; sc.Wl[l] = p->Wl[l]; }
     sc.bin_count = p->bin_count; sc.bin_off = p->bin_off; sc.items = p->items;
     sc.n_items = p->n_items; sc.stats = p->stats;
@@ -206,11 +206,12 @@ hipError_t launch_bin_stats(corr_pyramid* p, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipStream_t s) {
+hipError_t launch_binning(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s) {
     const int HW = p->H * p->W, BN = p->B * HW;
     BinArgs a;
-    a.coords = coords; a.out = out; a.B = p->B; a.HW = HW; a.L = p->L; a.g = p->grid;
-    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, p->grid.r);
+    a.coords = coords; a.out = out; a.B = p->B; a.HW = HW; a.L = p->L; a.r = r; a.g = p->grid;
+    p->last_r = r;
+    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, r);
     a.bin_count = p->bin_count; a.q_bin = p->q_bin; a.q_rank = p->q_rank;
     hipLaunchKernelGGL(bin_count_kernel, dim3((BN + 255) / 256), dim3(256), 0, s, a);
     hipError_t e = hipGetLastError();

@@ -30,7 +30,14 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int R = CORR_R, K = 2 * R + 1, KK = K * K;
+// This file is compiled once per lookup radius (CORR_BLOCK_R = 1..4): window sizes, LDS sizes and
+// the tap loops are compile-time functions of it.
+#ifndef CORR_BLOCK_R
+#define CORR_BLOCK_R CORR_R
+#endif
+#define CORR_CAT2(a, b) a##b
+#define CORR_CAT(a, b) CORR_CAT2(a, b)
+constexpr int R = CORR_BLOCK_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 constexpr int NW = 4, NT = 64 * NW;
 constexpr int XCD_RUN = 64;   // about one 8x8 super-tile of cells
@@ -228,7 +235,9 @@ __device__ __forceinline__ void write_taps(const BlockArgs& a, const ItemCtx& c,
         const float flx = floorf(cxl), fly = floorf(cyl);
         const float fx = cxl - flx, fy = cyl - fly;
         const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
-        const int i0 = wave == 0 ? 0 : 2 * wave + 1, i1 = 2 * wave + 3;   // 0..3, 3..5, 5..7, 7..9
+        // K = 9: columns 0..3, 3..5, 5..7, 7..9; otherwise an even split
+        const int i0 = K == 9 ? (wave == 0 ? 0 : 2 * wave + 1) : wave * K / NW;
+        const int i1 = K == 9 ? 2 * wave + 3 : (wave + 1) * K / NW;
         const float* s = S + (ry * G::WSX + rx + i0) * 64 + q;
         float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride + (size_t)(i0 * K) * tap_stride;
         float left[K + 1], right[K + 1];
@@ -457,7 +466,7 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
     BlockArgs a;
     a.f1s = p->f1_split; a.f2s = p->f2_split; a.coords = coords; a.perm = p->perm; a.items = p->items;
     a.n_items = p->n_items; a.out = out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L;
-    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, CORR_R);
+    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, R);
     a.g = p->grid;
     for (int l = 0; l < CORR_MAX_L; ++l) { a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; a.pix_base[l] = p->f2_pix_base[l]; }
     a.rec = (!THREE && (p->built & CORR_REP_BF16)) ? 32 : 64;      // bf16 mode prefers the hi-only records
@@ -471,7 +480,7 @@ hipError_t launch_items(corr_pyramid* p, const float* coords, float* out, hipStr
 
 }  // namespace
 
-hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s) {
+hipError_t CORR_CAT(launch_block_r, CORR_BLOCK_R)(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s) {
     const bool big = p->D > CORR_BLOCK_MAX_D, three = prec != CORR_PREC_BF16;
 #define CORR_LAUNCH(NHWC)                                                                                    \
     (three ? (big ? launch_items<true, true, NHWC>(p, coords, out, s) : launch_items<true, false, NHWC>(p, coords, out, s))   \

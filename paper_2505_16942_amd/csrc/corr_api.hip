@@ -249,16 +249,19 @@ corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_lay
     switch (mode) {
         case CORR_MODE_BLOCK: {
             if (prec != CORR_PREC_BF16X3 && prec != CORR_PREC_BF16) return CORR_ERR_INVALID_ARG;
-            if (r != 4) return CORR_ERR_UNSUPPORTED;
             if (!(pyr->built & (prec == CORR_PREC_BF16 ? (CORR_REP_SPLIT | CORR_REP_BF16) : CORR_REP_SPLIT)))
                 return CORR_ERR_MISSING_REP;
             hipEvent_t* ev = nullptr;
             if (pyr->prof_on && pyr->prof_ev && pyr->prof_n < CORR_PROF_LOOKUPS)
                 ev = pyr->prof_ev + (size_t)pyr->prof_n * 3;
             if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CORR_ERR_HIP;
-            e = launch_binning(pyr, coords, out, s);
+            e = launch_binning(pyr, coords, r, out, s);
             if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
-            if (e == hipSuccess) e = launch_block(pyr, coords, (int)prec, out, s);
+            if (e == hipSuccess)
+                e = r == 1 ? launch_block_r1(pyr, coords, (int)prec, out, s)
+                  : r == 2 ? launch_block_r2(pyr, coords, (int)prec, out, s)
+                  : r == 3 ? launch_block_r3(pyr, coords, (int)prec, out, s)
+                           : launch_block_r4(pyr, coords, (int)prec, out, s);
             if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
             if (ev && e == hipSuccess) pyr->prof_n++;
             break;

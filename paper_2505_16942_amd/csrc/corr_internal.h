@@ -9,7 +9,7 @@
 #define CORR_CHUNK 32          // channels per chunk plane of the split representation
 #define CORR_GROUP 64          // queries per work item
 #define CORR_BLOCK_MAX_D 256   // channels of query fragments a wave of the block kernel holds in registers at a time
-#define CORR_R 4               // radius the block kernels are built for
+#define CORR_R 4               // largest lookup radius; the cell grid is laid out for it
 #ifndef CORR_LOG_CX
 #define CORR_LOG_CX 3          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
 #endif
@@ -78,6 +78,7 @@ struct corr_pyramid {
     int vol_valid;
     size_t bytes;
     int out_nhwc;                  // layout of `out` for the call being enqueued (set by corr_sample_layout)
+    int last_r;                    // radius of the last block-mode lookup (for its work counters)
     // timing hook
     int prof_on, prof_n;
     hipEvent_t* prof_ev;           // [CORR_PROF_LOOKUPS][3]
@@ -107,9 +108,13 @@ static inline int corr_pix_stride(const corr_pyramid* p, int r) { return p->out_
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
                                  uint16_t* split, uint16_t* hi, float* const* nhwc, hipStream_t s);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s);
-hipError_t launch_binning(corr_pyramid* p, const float* coords, float* out, hipStream_t s);
+hipError_t launch_binning(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
 hipError_t launch_bin_stats(corr_pyramid* p, hipStream_t s);
-hipError_t launch_block(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
+// one instantiation of block.hip per lookup radius
+hipError_t launch_block_r1(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
+hipError_t launch_block_r2(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
+hipError_t launch_block_r3(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
+hipError_t launch_block_r4(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
 hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
 hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s);
 hipError_t launch_fullvol_sample(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);

@@ -206,12 +206,38 @@ def test_lookups_replayed_from_a_hip_graph():
 
 
 @pytest.mark.parametrize("r", [1, 2, 3])
-@pytest.mark.parametrize("mode", [1, 2])
-def test_other_radii_reference_modes(r, mode):
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_other_radii(r, mode):
     f1, f2, c = synth.small_case(7, 1, 19, 23, 64, flow_range=5.0)
     ref = oracle.lookup(f1, f2, c, L=3, r=r)
     res, _ = _run(f1, f2, c, 3, r, mode)
     _check(res, ref, FP32_TOL, "r=%d mode %d" % (r, mode))
+
+
+@pytest.mark.parametrize("r", [1, 2, 3])
+def test_other_radii_block_mode_four_levels_far_motion_and_layouts(r):
+    """Block mode at r < 4: four levels (fused coarse pass), windows partly outside, null queries,
+    bf16 mode and the channels-last layout."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 2, 33, 41, 96, 4
+    f1, f2, c = synth.small_case(80 + r, B, H, W, D, flow_range=25.0)
+    c[1, :, 2, 3] = np.float32(-1e6)
+    ref = oracle.lookup(f1, f2, c, L=L, r=r)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_SPLIT)
+    K = 2 * r + 1
+    out = torch.full((B, L * K * K, H, W), float("nan"), dtype=torch.float32, device=dev)
+    b.corr_sample(t1, pyr, tc, r=r, out=out)
+    _check(out.cpu().numpy(), ref, FP32_TOL, "block r=%d" % r)
+    stats = b.corr_last_block_stats(pyr)
+    assert stats["query_levels"] == B * H * W * L and 0 < stats["null_query_levels"] < B * H * W * L
+    o16 = b.corr_sample(t1, pyr, tc, r=r, prec=b.CORR_PREC_BF16)
+    _check(o16.cpu().numpy(), ref, BF16_TOL, "block bf16 r=%d" % r)
+    ocl = torch.full((B, H, W, L * K * K), float("nan"), dtype=torch.float32, device=dev)
+    b.corr_sample(t1, pyr, tc, r=r, out=ocl, layout=b.CORR_OUT_NHWC)
+    assert torch.equal(ocl.permute(0, 3, 1, 2), out)
+    pyr.destroy()
 
 
 def test_tiny_config_block_and_bf16():
@@ -291,7 +317,7 @@ def test_error_paths():
         b.corr_sample(f, pyr, c, mode=b.CORR_MODE_ONDEMAND)
     assert e.value.status == b.CORR_ERR_MISSING_REP
     with pytest.raises(b.CorrError) as e:
-        b.corr_sample(f, pyr, c, r=3)
+        b.corr_sample(f, pyr, c, r=5)
     assert e.value.status == b.CORR_ERR_UNSUPPORTED
     pyr.destroy()
     # the 8K dense volume is reported, not run
