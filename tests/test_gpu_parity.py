@@ -278,6 +278,28 @@ def test_special_coordinates():
         assert np.all(res[0, :, 0, :5] == 0.0)
 
 
+@pytest.mark.parametrize("fill", ["nan", "far"])
+def test_no_query_in_range(fill):
+    """Degenerate lookup: every query is out of range at every level, so there is no work item at
+    all; every output is written as zero, and the next ordinary lookup on the pyramid is unaffected."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 2, 20, 28, 64, 4
+    f1, f2, c = synth.small_case(91, B, H, W, D, flow_range=6.0)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    bad = torch.full_like(tc, float("nan") if fill == "nan" else 5000.0)
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=3)
+    for mode in (0, 1):
+        for layout, shape in ((b.CORR_OUT_NCHW, (B, L * 81, H, W)), (b.CORR_OUT_NHWC, (B, H, W, L * 81))):
+            out = torch.full(shape, float("nan"), dtype=torch.float32, device=dev)
+            b.corr_sample(t1, pyr, bad, out=out, mode=mode, layout=layout)
+            assert torch.count_nonzero(out).item() == 0 and not torch.isnan(out).any()
+    assert b.corr_last_block_stats(pyr)["items"] == 0
+    ref = oracle.lookup(f1, f2, c, L=L, r=4)
+    _check(b.corr_sample(t1, pyr, tc).cpu().numpy(), ref, FP32_TOL, "lookup after an empty one")
+    pyr.destroy()
+
+
 def test_determinism_and_pyramid_reuse():
     b = _binding()
     dev = torch.device("cuda:0")
