@@ -102,20 +102,20 @@ def main() -> int:
     stats = []
     for tc in tcs:
         cb.corr_sample(t1, pyr, tc, r=r, out=out, prec=prec, layout=layout)
-        stats.append(cb.corr_last_block_stats(pyr))
+        stats.append(cb.corr_last_block_stats(pyr, r))
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
-    cb.corr_profile_enable(pyr, True)
+    cb.corr_profile_enable(True)
     torch.cuda.synchronize()
     tb = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     te = time.perf_counter()
-    prof = cb.corr_profile_read(pyr)
-    cb.corr_profile_enable(pyr, False)
+    prof = cb.corr_profile_read()
+    cb.corr_profile_enable(False)
 
     ms_per_step = (te - tb) * 1e3 / args.steps
     lookups_per_call = B * N * L * K * K

@@ -85,8 +85,9 @@ corr_status corr_pyramid_build(const float* fmap1, const float* fmap2,
 corr_status corr_pyramid_build_reps(const float* fmap1, const float* fmap2,
                                     int B, int H, int W, int D, int L, unsigned reps,
                                     corr_pyramid** pyr, void* stream);
-/* Synchronises the device, then frees everything the pyramid owns.  NULL is accepted. */
-corr_status corr_pyramid_destroy(corr_pyramid* pyr);
+/* Waits for the work enqueued on `stream` (the stream the pyramid's builds and lookups were
+ * ordered on), then frees everything the pyramid owns.  NULL is accepted. */
+corr_status corr_pyramid_destroy(corr_pyramid* pyr, void* stream);
 /* Device bytes currently owned by the pyramid (features, workspace, cached dense volume). */
 size_t corr_pyramid_bytes(const corr_pyramid* pyr);
 
@@ -99,16 +100,19 @@ size_t corr_pyramid_bytes(const corr_pyramid* pyr);
  *             level-0 pixels of fmap2.
  *   r       : lookup radius; 1 <= r <= 4 in every mode.
  *   out     : device fp32 [B, L*(2r+1)^2, H, W], fully overwritten (no need to zero it).
- * Allocates nothing, except CORR_MODE_FULLVOLUME on its first call for a pyramid build (the dense
- * volume, cached in the pyramid until the next build or destroy).  Work is enqueued on `stream`;
- * calls that share a pyramid must be ordered on one stream (they share its workspace).
+ * Nothing about a call is kept in the pyramid: radius, layout and precision travel with the
+ * launch.  The pyramid is const here with one documented exception, a lazily built
+ * representation: CORR_MODE_FULLVOLUME allocates and fills the dense volume on its first call
+ * after a build and caches it in the pyramid until the next build or destroy.  Every other call
+ * allocates nothing.  Work is enqueued on `stream`; calls that share a pyramid must be ordered
+ * on one stream (they share its planning workspace).
  * corr_sample == corr_sample_mode(CORR_MODE_BLOCK, CORR_PREC_BF16X3, ...).
  */
-corr_status corr_sample(const float* fmap1, corr_pyramid* pyr, const float* coords,
+corr_status corr_sample(const float* fmap1, const corr_pyramid* pyr, const float* coords,
                         int B, int H, int W, int D, int L, int r,
                         float* out, void* stream);
 corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
-                             const float* fmap1, corr_pyramid* pyr, const float* coords,
+                             const float* fmap1, const corr_pyramid* pyr, const float* coords,
                              int B, int H, int W, int D, int L, int r,
                              float* out, void* stream);
 
@@ -122,65 +126,25 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
  */
 typedef enum { CORR_OUT_NCHW = 0, CORR_OUT_NHWC = 1 } corr_out_layout;
 corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_layout layout,
-                               const float* fmap1, corr_pyramid* pyr, const float* coords,
+                               const float* fmap1, const corr_pyramid* pyr, const float* coords,
                                int B, int H, int W, int D, int L, int r, float* out, void* hip_stream);
 
 /* Exact size of the dense volume pyramid of Eq. 2: 4 * B * (H*W) * sum_l(H_l*W_l) bytes
  * (0 if a level is empty or L is out of range).  Pure host arithmetic. */
 size_t corr_full_volume_bytes(int B, int H, int W, int L);
-/* Device bytes corr_pyramid_build_reps would allocate for these sizes (features + workspace). */
-size_t corr_workspace_bytes(unsigned reps, int B, int H, int W, int D, int L);
-
 /*
- * Counters of the last CORR_MODE_BLOCK call on this pyramid (written by the binning pass).
- * Synchronises `stream` and copies them to the host.
- *   items            work items = (target cell, group of <= 64 of its queries) pairs
- *   query_levels     B*H*W*L
- *   null_query_levels  query-levels whose cell window lies wholly outside the level (written as zeros,
- *                      no contraction)
- *   mma_point_queries  sum over items of window points x queries padded to 16: the contraction
- *                      work actually issued is 2*D*mma_point_queries flop per bf16 term
- *   used_point_queries sum over items of window points x real queries
+ * Device bytes the library holds for one image pair in `mode` with lookup radius r, beyond the
+ * caller's inputs and outputs (paper Eq. 4, "Memory Complexity Analysis": the extra space of the
+ * method is linear in the number of pixels P; the dense volume of Eq. 2 is quadratic):
+ *   CORR_MODE_BLOCK      re-laid bf16 hi/lo features of fmap1 and of every level of fmap2
+ *                        (4*D bytes per pixel) + the planning workspace (cell counters, three ints
+ *                        per query, the item list): O(P * (D + 1)), independent of r
+ *   CORR_MODE_ONDEMAND   channels-last fp32 features (4*D bytes per pixel): O(P * D)
+ *   CORR_MODE_FULLVOLUME the same + corr_full_volume_bytes(): O(P^2)
+ * 0 for unsupported sizes.  Pure host arithmetic; matches what corr_pyramid_bytes() reports after
+ * a build with the representation that mode reads (and, for FULLVOLUME, one lookup).
  */
-typedef struct {
-    int64_t items;
-    int64_t query_levels;
-    int64_t null_query_levels;
-    int64_t mma_point_queries;
-    int64_t used_point_queries;
-    /* the same, per level (entries >= L are zero); level_queries = query-levels that reached the contraction */
-    int64_t level_items[4];
-    int64_t level_mma_point_queries[4];
-    int64_t level_used_point_queries[4];
-    int64_t level_queries[4];
-} corr_block_stats;
-corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, void* stream);
-
-/*
- * Timing hook for benchmarks.  While enabled, every CORR_MODE_BLOCK call records HIP events on its
- * stream before the binning pass, after it, and after the block kernel (up to 256
- * lookups between two reads; later ones are not recorded).  corr_profile_read waits for the recorded
- * events, returns the sums of elapsed milliseconds and the number of lookups they cover, and resets.
- */
-typedef struct {
-    int64_t lookups;
-    double binning_ms;
-    double block_ms;         /* contraction + epilogue kernel (all levels) */
-} corr_profile;
-corr_status corr_profile_enable(corr_pyramid* pyr, int enable);
-corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof);
-
-/* Host-side test hook of the binning rule (no device work).  Queries are grouped by the cell
- * (floor(x) >> 3, floor(y) >> 3) of their level-0 target; for level l < L this returns the side of a
- * cell in level-l pixels (max(8 >> l, 1)), the window of target pixels a cell owns at that level
- * (cell + 2*4 + 1 per axis) and the number of cells per axis of the grid (it extends past the image
- * as far as the coarsest level is in range). */
-corr_status corr_bin_geometry(int H, int W, int L, int l, int* cell_x, int* cell_y,
-                              int* window_x, int* window_y, int* cells_x, int* cells_y);
-
-/* Measurement aid: a plain grid-stride copy of n floats (device to device) on `stream`.  Profiling
- * runs use it as the kernel of known size against which the HBM byte counters are scaled. */
-corr_status corr_copy_f32(float* dst, const float* src, size_t n, void* stream);
+size_t corr_workspace_bytes(corr_mode mode, int B, int H, int W, int D, int L, int r);
 
 const char* corr_status_string(corr_status s);
 

@@ -1,4 +1,4 @@
-"""Thin Python binding of the C-ABI library (include/corr.h).
+"""Thin Python binding of the C-ABI library (include/corr.h, include/corr_bench.h).
 
 Argument marshalling only: every step of the lookup runs in the library's HIP
 kernels.  PyTorch supplies device memory and the current stream.  There is no
@@ -21,11 +21,16 @@ CORR_PREC_BF16X3, CORR_PREC_BF16 = 0, 1
 CORR_OUT_NCHW, CORR_OUT_NHWC = 0, 1
 CORR_REP_SPLIT, CORR_REP_F32, CORR_REP_BF16 = 1, 2, 4
 
+# the method's boundary (include/corr.h)
 EXPORTS = [
     "corr_pyramid_build", "corr_pyramid_build_reps", "corr_pyramid_destroy", "corr_pyramid_bytes",
-    "corr_sample", "corr_sample_mode", "corr_sample_layout", "corr_full_volume_bytes", "corr_workspace_bytes",
-    "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry",
-    "corr_copy_f32", "corr_status_string",
+    "corr_sample", "corr_sample_mode", "corr_sample_layout",
+    "corr_full_volume_bytes", "corr_workspace_bytes", "corr_status_string",
+]
+# measurement and test hooks (include/corr_bench.h)
+BENCH_EXPORTS = [
+    "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry", "corr_copy_f32",
+    "corr_debug_read_plan", "corr_debug_cell_coords", "corr_debug_read_level",
 ]
 
 
@@ -44,7 +49,8 @@ class BlockStats(ctypes.Structure):
 
 
 class Profile(ctypes.Structure):
-    _fields_ = [("lookups", ctypes.c_int64), ("binning_ms", ctypes.c_double), ("block_ms", ctypes.c_double)]
+    _fields_ = [("lookups", ctypes.c_int64), ("dropped", ctypes.c_int64),
+                ("binning_ms", ctypes.c_double), ("block_ms", ctypes.c_double)]
 
 
 _lib = None
@@ -63,7 +69,7 @@ def load_library():
     lib.corr_pyramid_build.restype = ci
     lib.corr_pyramid_build_reps.argtypes = [vp, vp, ci, ci, ci, ci, ci, cu, ctypes.POINTER(vp), vp]
     lib.corr_pyramid_build_reps.restype = ci
-    lib.corr_pyramid_destroy.argtypes = [vp]
+    lib.corr_pyramid_destroy.argtypes = [vp, vp]
     lib.corr_pyramid_destroy.restype = ci
     lib.corr_pyramid_bytes.argtypes = [vp]
     lib.corr_pyramid_bytes.restype = sz
@@ -75,18 +81,25 @@ def load_library():
     lib.corr_sample_layout.restype = ci
     lib.corr_full_volume_bytes.argtypes = [ci, ci, ci, ci]
     lib.corr_full_volume_bytes.restype = sz
-    lib.corr_workspace_bytes.argtypes = [cu, ci, ci, ci, ci, ci]
+    lib.corr_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci]
     lib.corr_workspace_bytes.restype = sz
-    lib.corr_last_block_stats.argtypes = [vp, ctypes.POINTER(BlockStats), vp]
+    lib.corr_last_block_stats.argtypes = [vp, ci, ctypes.POINTER(BlockStats), vp]
     lib.corr_last_block_stats.restype = ci
-    lib.corr_profile_enable.argtypes = [vp, ci]
+    lib.corr_profile_enable.argtypes = [ci]
     lib.corr_profile_enable.restype = ci
-    lib.corr_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
+    lib.corr_profile_read.argtypes = [ctypes.POINTER(Profile)]
     lib.corr_profile_read.restype = ci
     lib.corr_bin_geometry.argtypes = [ci, ci, ci, ci] + [ctypes.POINTER(ci)] * 6
     lib.corr_bin_geometry.restype = ci
     lib.corr_copy_f32.argtypes = [vp, vp, sz, vp]
     lib.corr_copy_f32.restype = ci
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.corr_debug_read_plan.argtypes = [vp, i32p, i32p, sz, i32p, sz, vp]
+    lib.corr_debug_read_plan.restype = ci
+    lib.corr_debug_cell_coords.argtypes = [vp, ci] + [ctypes.POINTER(ci)] * 3
+    lib.corr_debug_cell_coords.restype = ci
+    lib.corr_debug_read_level.argtypes = [vp, cu, ci, ctypes.POINTER(ctypes.c_float), vp]
+    lib.corr_debug_read_level.restype = ci
     lib.corr_status_string.argtypes = [ci]
     lib.corr_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -101,8 +114,8 @@ def corr_full_volume_bytes(B: int, H: int, W: int, L: int) -> int:
     return int(load_library().corr_full_volume_bytes(B, H, W, L))
 
 
-def corr_workspace_bytes(reps: int, B: int, H: int, W: int, D: int, L: int) -> int:
-    return int(load_library().corr_workspace_bytes(reps, B, H, W, D, L))
+def corr_workspace_bytes(mode: int, B: int, H: int, W: int, D: int, L: int, r: int = 4) -> int:
+    return int(load_library().corr_workspace_bytes(mode, B, H, W, D, L, r))
 
 
 def corr_bin_geometry(H: int, W: int, L: int, l: int):
@@ -123,6 +136,13 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+def _stream_or_null():
+    try:
+        return torch.cuda.current_stream().cuda_stream
+    except Exception:      # interpreter shutdown
+        return None
+
+
 class Pyramid:
     """Owner of a library pyramid handle."""
 
@@ -135,7 +155,7 @@ class Pyramid:
 
     def destroy(self):
         if self.handle is not None and self.handle.value:
-            load_library().corr_pyramid_destroy(self.handle)
+            load_library().corr_pyramid_destroy(self.handle, _stream_or_null())
         self.handle = None
 
     def __del__(self):
@@ -186,9 +206,9 @@ def corr_sample(fmap1, pyramid: Pyramid, coords: torch.Tensor, r: int = 4,
     return out
 
 
-def corr_last_block_stats(pyramid: Pyramid) -> dict:
+def corr_last_block_stats(pyramid: Pyramid, r: int = 4) -> dict:
     s = BlockStats()
-    st = load_library().corr_last_block_stats(pyramid.handle, ctypes.byref(s), _stream())
+    st = load_library().corr_last_block_stats(pyramid.handle, r, ctypes.byref(s), _stream())
     if st != CORR_OK:
         raise CorrError(st, "corr_last_block_stats")
     out = {}
@@ -208,15 +228,51 @@ def corr_copy_f32(dst: torch.Tensor, src: torch.Tensor) -> None:
         raise CorrError(st, "corr_copy_f32")
 
 
-def corr_profile_enable(pyramid: Pyramid, enable: bool = True) -> None:
-    st = load_library().corr_profile_enable(pyramid.handle, 1 if enable else 0)
+def corr_profile_enable(enable: bool = True) -> None:
+    st = load_library().corr_profile_enable(1 if enable else 0)
     if st != CORR_OK:
         raise CorrError(st, "corr_profile_enable")
 
 
-def corr_profile_read(pyramid: Pyramid) -> dict:
+def corr_profile_read() -> dict:
     p = Profile()
-    st = load_library().corr_profile_read(pyramid.handle, ctypes.byref(p))
+    st = load_library().corr_profile_read(ctypes.byref(p))
     if st != CORR_OK:
         raise CorrError(st, "corr_profile_read")
-    return {"lookups": int(p.lookups), "binning_ms": float(p.binning_ms), "block_ms": float(p.block_ms)}
+    return {"lookups": int(p.lookups), "dropped": int(p.dropped),
+            "binning_ms": float(p.binning_ms), "block_ms": float(p.block_ms)}
+
+
+def corr_debug_read_plan(pyramid: Pyramid):
+    """(items [n, 4] int32, perm [m] int32) of the last block-mode lookup on this pyramid."""
+    import numpy as np
+    BN = pyramid.B * pyramid.H * pyramid.W
+    counts = np.zeros(2, np.int32)
+    items = np.zeros((BN + 65536, 4), np.int32)
+    perm = np.zeros(BN, np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    st = load_library().corr_debug_read_plan(pyramid.handle, counts.ctypes.data_as(i32p), items.ctypes.data_as(i32p),
+                                             items.shape[0], perm.ctypes.data_as(i32p), perm.size, _stream())
+    if st != CORR_OK:
+        raise CorrError(st, "corr_debug_read_plan")
+    return items[:counts[0]].copy(), perm[:counts[1]].copy()
+
+
+def corr_debug_cell_coords(pyramid: Pyramid, cell_id: int):
+    vals = [ctypes.c_int() for _ in range(3)]
+    st = load_library().corr_debug_cell_coords(pyramid.handle, int(cell_id), *[ctypes.byref(v) for v in vals])
+    if st != CORR_OK:
+        raise CorrError(st, "corr_debug_cell_coords")
+    return tuple(v.value for v in vals)    # b, u, v
+
+
+def corr_debug_read_level(pyramid: Pyramid, rep: int, level: int):
+    """Level `level` of fmap2 (-1: fmap1) as the pyramid holds it: fp32 [B, H_l, W_l, D] numpy array."""
+    import numpy as np
+    Hl, Wl = (pyramid.H, pyramid.W) if level < 0 else (pyramid.H >> level, pyramid.W >> level)
+    dst = np.zeros((pyramid.B, Hl, Wl, pyramid.D), np.float32)
+    st = load_library().corr_debug_read_level(pyramid.handle, rep, level,
+                                              dst.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), _stream())
+    if st != CORR_OK:
+        raise CorrError(st, "corr_debug_read_level")
+    return dst

@@ -2,6 +2,7 @@
 // pyramid object and its device allocations, and the order in which the kernels
 // of one build / one lookup are enqueued.
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 #include "corr_internal.h"
 
@@ -20,15 +21,13 @@ corr_status check_dims(int B, int H, int W, int D, int L) {
     long long px = 0;
     for (int l = 0; l < L; ++l) px += (long long)(H >> l) * (W >> l);
     if ((long long)B * px * D * 2 >= (1LL << 31)) return CORR_ERR_UNSUPPORTED;   // 32-bit element offsets
+    if ((long long)B * px * D * 4 >= (1LL << 31)) return CORR_ERR_UNSUPPORTED;   // byte offsets into the split pyramid
     return CORR_OK;
 }
 
 void fill_geometry(corr_pyramid* p) {
-    const int BN = p->B * p->H * p->W;
     for (int l = 0; l < CORR_MAX_L; ++l) { p->Hl[l] = p->H >> l; p->Wl[l] = p->W >> l; }
-    corr_fill_grid(&p->grid, p->H, p->W, p->L, CORR_R);
-    p->nbins = p->B * 64 * p->grid.tnx * p->grid.tny;
-    p->max_items = BN / CORR_GROUP + (p->nbins < BN ? p->nbins : BN) + 1;
+    corr_fill_grid(&p->grid, p->H, p->W, p->L);
 }
 
 template <typename T>
@@ -56,12 +55,7 @@ void free_all(corr_pyramid* p) {
     (void)hipFree(p->f1_nhwc); (void)hipFree(p->f1_split);
     for (int l = 0; l < CORR_MAX_L; ++l) (void)hipFree(p->f2_nhwc[l]);
     (void)hipFree(p->f2_split); (void)hipFree(p->f1_hi); (void)hipFree(p->f2_hi);
-    (void)hipFree(p->bin_count); (void)hipFree(p->bin_off); (void)hipFree(p->q_bin); (void)hipFree(p->q_rank);
-    if (p->prof_ev) {
-        for (int i = 0; i < CORR_PROF_LOOKUPS * 3; ++i) (void)hipEventDestroy(p->prof_ev[i]);
-        delete[] p->prof_ev;
-    }
-    (void)hipFree(p->perm); (void)hipFree(p->items); (void)hipFree(p->n_items); (void)hipFree(p->stats);
+    (void)hipFree(p->ws_mem);
     delete p;
 }
 
@@ -101,19 +95,14 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
             need(dev_alloc(&p->f1_hi, BN * D, &p->bytes));
             need(dev_alloc(&p->f2_hi, px * D, &p->bytes));
         }
-        need(dev_alloc(&p->bin_count, (size_t)p->nbins, &p->bytes));
-        need(dev_alloc(&p->bin_off, (size_t)p->nbins, &p->bytes));
-        need(dev_alloc(&p->q_bin, BN, &p->bytes));
-        need(dev_alloc(&p->q_rank, BN, &p->bytes));
-        need(dev_alloc(&p->perm, BN, &p->bytes));
-        need(dev_alloc(&p->items, (size_t)p->max_items, &p->bytes));
-        need(dev_alloc(&p->n_items, (size_t)4, &p->bytes));
-        need(dev_alloc(&p->stats, (size_t)CORR_NSTATS, &p->bytes));
+        const int ncells = corr_ncells(p->grid, B);
+        const WsLayout wl = corr_ws_layout((int)BN, ncells);
+        unsigned char* mem = nullptr;
+        need(dev_alloc(&mem, wl.total, &p->bytes));
         if (st == CORR_OK) {
-            if (hipMemset(p->bin_count, 0, sizeof(int) * p->nbins) != hipSuccess ||
-                hipMemset(p->stats, 0, sizeof(long long) * CORR_NSTATS) != hipSuccess ||
-                hipMemset(p->n_items, 0, sizeof(int) * 4) != hipSuccess)
-                st = CORR_ERR_HIP;
+            p->ws_mem = mem;
+            p->ws = corr_ws_carve(mem, (int)BN, ncells);
+            if (hipMemset(mem, 0, wl.total) != hipSuccess) st = CORR_ERR_HIP;   // counters start at zero
         }
     }
     if (st != CORR_OK) { free_all(p); return st; }
@@ -124,6 +113,49 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
 corr_status check_against(const corr_pyramid* p, int B, int H, int W, int D, int L) {
     if (!p) return CORR_ERR_INVALID_ARG;
     if (p->B != B || p->H != H || p->W != W || p->D != D || p->L != L) return CORR_ERR_INVALID_ARG;
+    return CORR_OK;
+}
+
+
+// ---- process-wide timing hook (measurement only)
+constexpr int PROF_LOOKUPS = 256;
+struct Profiler {
+    int on = 0, n = 0;
+    long long dropped = 0;
+    hipEvent_t* ev = nullptr;      // [PROF_LOOKUPS][3]
+} g_prof;
+
+hipError_t launch_block(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s) {
+    return q.r == 1 ? launch_block_r1(p, ws, q, s)
+         : q.r == 2 ? launch_block_r2(p, ws, q, s)
+         : q.r == 3 ? launch_block_r3(p, ws, q, s)
+                    : launch_block_r4(p, ws, q, s);
+}
+
+// planning pass + block kernel on workspace `ws`
+hipError_t enqueue_block_lookup(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s) {
+    hipEvent_t* ev = nullptr;
+    if (g_prof.on && g_prof.ev) {
+        if (g_prof.n < PROF_LOOKUPS) ev = g_prof.ev + (size_t)g_prof.n * 3;
+        else g_prof.dropped++;
+    }
+    hipError_t e = hipSuccess;
+    if (ev) e = hipEventRecord(ev[0], s);
+    if (e == hipSuccess) e = launch_binning(p, ws, q, s);
+    if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
+    if (e == hipSuccess) e = launch_block(p, ws, q, s);
+    if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
+    if (ev && e == hipSuccess) g_prof.n++;
+    return e;
+}
+
+corr_status check_lookup_args(const corr_pyramid* pyr, const float* coords, const float* out,
+                              int B, int H, int W, int D, int L, int r) {
+    if (!pyr || !coords || !out) return CORR_ERR_INVALID_ARG;
+    corr_status st = check_against(pyr, B, H, W, D, L);
+    if (st != CORR_OK) return st;
+    if (r < 1) return CORR_ERR_INVALID_ARG;
+    if (r > CORR_R) return CORR_ERR_UNSUPPORTED;
     return CORR_OK;
 }
 
@@ -150,18 +182,18 @@ size_t corr_full_volume_bytes(int B, int H, int W, int L) {
     return (size_t)4 * B * H * W * px;
 }
 
-size_t corr_workspace_bytes(unsigned reps, int B, int H, int W, int D, int L) {
-    if (check_dims(B, H, W, D, L) != CORR_OK) return 0;
-    size_t bytes = feature_bytes(reps, B, H, W, D, L);
-    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16)) {
-        corr_pyramid tmp;
-        memset(&tmp, 0, sizeof(tmp));
-        tmp.B = B; tmp.H = H; tmp.W = W; tmp.D = D; tmp.L = L;
-        fill_geometry(&tmp);
-        const size_t BN = (size_t)B * H * W;
-        bytes += (size_t)tmp.nbins * 8 + BN * 12 + (size_t)tmp.max_items * 16 + 16 + CORR_NSTATS * 8;
+size_t corr_workspace_bytes(corr_mode mode, int B, int H, int W, int D, int L, int r) {
+    if (check_dims(B, H, W, D, L) != CORR_OK || r < 1 || r > CORR_R) return 0;
+    switch (mode) {
+        case CORR_MODE_BLOCK: {
+            CellGrid g;
+            corr_fill_grid(&g, H, W, L);
+            return feature_bytes(CORR_REP_SPLIT, B, H, W, D, L) + corr_ws_layout(B * H * W, corr_ncells(g, B)).total;
+        }
+        case CORR_MODE_ONDEMAND: return feature_bytes(CORR_REP_F32, B, H, W, D, L);
+        case CORR_MODE_FULLVOLUME: return feature_bytes(CORR_REP_F32, B, H, W, D, L) + corr_full_volume_bytes(B, H, W, L);
     }
-    return bytes;
+    return 0;
 }
 
 size_t corr_pyramid_bytes(const corr_pyramid* pyr) { return pyr ? pyr->bytes : 0; }
@@ -170,9 +202,9 @@ corr_status corr_bin_geometry(int H, int W, int L, int l, int* cell_x, int* cell
                               int* cells_x, int* cells_y) {
     if (H <= 0 || W <= 0 || !level_sizes_ok(H, W, L) || l < 0 || l >= L) return CORR_ERR_INVALID_ARG;
     CellGrid g;
-    corr_fill_grid(&g, H, W, L, CORR_R);
-    const int cx = ((1 << g.log_cx) >> l) > 1 ? ((1 << g.log_cx) >> l) : 1;
-    const int cy = ((1 << g.log_cy) >> l) > 1 ? ((1 << g.log_cy) >> l) : 1;
+    corr_fill_grid(&g, H, W, L);
+    const int cx = ((1 << CORR_LOG_CX) >> l) > 1 ? ((1 << CORR_LOG_CX) >> l) : 1;
+    const int cy = ((1 << CORR_LOG_CY) >> l) > 1 ? ((1 << CORR_LOG_CY) >> l) : 1;
     if (cell_x) *cell_x = cx;
     if (cell_y) *cell_y = cy;
     if (window_x) *window_x = cx + 2 * CORR_R + 1;
@@ -220,75 +252,64 @@ corr_status corr_pyramid_build(const float* fmap1, const float* fmap2, int B, in
     return corr_pyramid_build_reps(fmap1, fmap2, B, H, W, D, L, CORR_REP_SPLIT, pyr, stream);
 }
 
-corr_status corr_pyramid_destroy(corr_pyramid* pyr) {
+corr_status corr_pyramid_destroy(corr_pyramid* pyr, void* stream) {
     if (!pyr) return CORR_OK;
-    const hipError_t e = hipDeviceSynchronize();
+    const hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
     free_all(pyr);
     return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 
-corr_status corr_sample_mode(corr_mode mode, corr_precision prec, const float* fmap1, corr_pyramid* pyr,
+corr_status corr_sample_mode(corr_mode mode, corr_precision prec, const float* fmap1, const corr_pyramid* pyr,
                              const float* coords, int B, int H, int W, int D, int L, int r,
                              float* out, void* stream) {
     return corr_sample_layout(mode, prec, CORR_OUT_NCHW, fmap1, pyr, coords, B, H, W, D, L, r, out, stream);
 }
 
 corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_layout layout, const float* fmap1,
-                               corr_pyramid* pyr, const float* coords, int B, int H, int W, int D, int L, int r,
+                               const corr_pyramid* pyr, const float* coords, int B, int H, int W, int D, int L, int r,
                                float* out, void* stream) {
     (void)fmap1;
-    if (!pyr || !coords || !out) return CORR_ERR_INVALID_ARG;
     if (layout != CORR_OUT_NCHW && layout != CORR_OUT_NHWC) return CORR_ERR_INVALID_ARG;
-    corr_status st = check_against(pyr, B, H, W, D, L);
+    corr_status st = check_lookup_args(pyr, coords, out, B, H, W, D, L, r);
     if (st != CORR_OK) return st;
-    if (r < 1) return CORR_ERR_INVALID_ARG;
-    if (r > 4) return CORR_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
-    pyr->out_nhwc = layout == CORR_OUT_NHWC;       // read by the launchers below
+    LookupArgs q;
+    q.coords = coords; q.out = out; q.r = r; q.nhwc = layout == CORR_OUT_NHWC; q.prec = (int)prec;
     switch (mode) {
         case CORR_MODE_BLOCK: {
             if (prec != CORR_PREC_BF16X3 && prec != CORR_PREC_BF16) return CORR_ERR_INVALID_ARG;
             if (!(pyr->built & (prec == CORR_PREC_BF16 ? (CORR_REP_SPLIT | CORR_REP_BF16) : CORR_REP_SPLIT)))
                 return CORR_ERR_MISSING_REP;
-            hipEvent_t* ev = nullptr;
-            if (pyr->prof_on && pyr->prof_ev && pyr->prof_n < CORR_PROF_LOOKUPS)
-                ev = pyr->prof_ev + (size_t)pyr->prof_n * 3;
-            if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CORR_ERR_HIP;
-            e = launch_binning(pyr, coords, r, out, s);
-            if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
-            if (e == hipSuccess)
-                e = r == 1 ? launch_block_r1(pyr, coords, (int)prec, out, s)
-                  : r == 2 ? launch_block_r2(pyr, coords, (int)prec, out, s)
-                  : r == 3 ? launch_block_r3(pyr, coords, (int)prec, out, s)
-                           : launch_block_r4(pyr, coords, (int)prec, out, s);
-            if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
-            if (ev && e == hipSuccess) pyr->prof_n++;
+            e = enqueue_block_lookup(pyr, pyr->ws, q, s);
             break;
         }
         case CORR_MODE_ONDEMAND: {
             if (!(pyr->built & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
-            e = launch_ondemand(pyr, coords, r, out, s);
+            e = launch_ondemand(pyr, q, s);
             break;
         }
         case CORR_MODE_FULLVOLUME: {
             if (!(pyr->built & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
             if (!pyr->vol_valid) {
-                if (!pyr->vol[0]) {
+                // the dense volume is a lazily built representation of the pair: the one part of the
+                // pyramid a lookup may fill in
+                corr_pyramid* mp = const_cast<corr_pyramid*>(pyr);
+                if (!mp->vol[0]) {
                     const size_t need = corr_full_volume_bytes(B, H, W, L);
                     size_t free_b = 0, total_b = 0;
                     if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) return CORR_ERR_HIP;
                     if (need + (256u << 20) > free_b) return CORR_ERR_OOM;
                     for (int l = 0; l < L; ++l) {
-                        st = dev_alloc(&pyr->vol[l], (size_t)B * H * W * pyr->Hl[l] * pyr->Wl[l], &pyr->bytes);
-                        if (st != CORR_OK) { free_volume(pyr); return st; }
+                        st = dev_alloc(&mp->vol[l], (size_t)B * H * W * mp->Hl[l] * mp->Wl[l], &mp->bytes);
+                        if (st != CORR_OK) { free_volume(mp); return st; }
                     }
                 }
-                e = launch_fullvol_build(pyr, s);
+                e = launch_fullvol_build(mp, s);
                 if (e != hipSuccess) break;
-                pyr->vol_valid = 1;
+                mp->vol_valid = 1;
             }
-            e = launch_fullvol_sample(pyr, coords, r, out, s);
+            e = launch_fullvol_sample(pyr, q, s);
             break;
         }
         default: return CORR_ERR_INVALID_ARG;
@@ -296,20 +317,20 @@ corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_lay
     return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 
-corr_status corr_sample(const float* fmap1, corr_pyramid* pyr, const float* coords,
+corr_status corr_sample(const float* fmap1, const corr_pyramid* pyr, const float* coords,
                         int B, int H, int W, int D, int L, int r, float* out, void* stream) {
     return corr_sample_mode(CORR_MODE_BLOCK, CORR_PREC_BF16X3, fmap1, pyr, coords, B, H, W, D, L, r, out, stream);
 }
 
-corr_status corr_last_block_stats(corr_pyramid* pyr, corr_block_stats* stats, void* stream) {
-    if (!pyr || !stats) return CORR_ERR_INVALID_ARG;
+corr_status corr_last_block_stats(const corr_pyramid* pyr, int r, corr_block_stats* stats, void* stream) {
+    if (!pyr || !stats || r < 1 || r > CORR_R) return CORR_ERR_INVALID_ARG;
     if (!(pyr->reps & (CORR_REP_SPLIT | CORR_REP_BF16))) return CORR_ERR_MISSING_REP;
     long long h[CORR_NSTATS];
     int hn[4];
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (launch_bin_stats(pyr, s) != hipSuccess) return CORR_ERR_HIP;
-    if (hipMemcpyAsync(h, pyr->stats, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
-    if (hipMemcpyAsync(hn, pyr->n_items, sizeof(hn), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
+    if (launch_bin_stats(pyr, pyr->ws, r, s) != hipSuccess) return CORR_ERR_HIP;
+    if (hipMemcpyAsync(h, pyr->ws.stats, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
+    if (hipMemcpyAsync(hn, pyr->ws.n_items, sizeof(hn), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return CORR_ERR_HIP;
     h[0] = hn[0];
     h[1] = (long long)pyr->B * pyr->H * pyr->W * pyr->L;
@@ -333,30 +354,30 @@ corr_status corr_copy_f32(float* dst, const float* src, size_t n, void* stream) 
     return launch_copy_f32(dst, src, n, static_cast<hipStream_t>(stream)) == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 
-corr_status corr_profile_enable(corr_pyramid* pyr, int enable) {
-    if (!pyr) return CORR_ERR_INVALID_ARG;
-    if (enable && !pyr->prof_ev) {
-        const int n = CORR_PROF_LOOKUPS * 3;
-        pyr->prof_ev = new (std::nothrow) hipEvent_t[n];
-        if (!pyr->prof_ev) return CORR_ERR_OOM;
+corr_status corr_profile_enable(int enable) {
+    if (enable && !g_prof.ev) {
+        const int n = PROF_LOOKUPS * 3;
+        g_prof.ev = new (std::nothrow) hipEvent_t[n];
+        if (!g_prof.ev) return CORR_ERR_OOM;
         for (int i = 0; i < n; ++i)
-            if (hipEventCreate(&pyr->prof_ev[i]) != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipEventDestroy(pyr->prof_ev[j]);
-                delete[] pyr->prof_ev; pyr->prof_ev = nullptr;
+            if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+                delete[] g_prof.ev; g_prof.ev = nullptr;
                 return CORR_ERR_HIP;
             }
     }
-    pyr->prof_on = enable ? 1 : 0;
-    pyr->prof_n = 0;
+    g_prof.on = enable ? 1 : 0;
+    g_prof.n = 0;
+    g_prof.dropped = 0;
     return CORR_OK;
 }
 
-corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof) {
-    if (!pyr || !prof) return CORR_ERR_INVALID_ARG;
+corr_status corr_profile_read(corr_profile* prof) {
+    if (!prof) return CORR_ERR_INVALID_ARG;
     memset(prof, 0, sizeof(*prof));
-    if (!pyr->prof_ev) return CORR_OK;
-    for (int i = 0; i < pyr->prof_n; ++i) {
-        hipEvent_t* ev = pyr->prof_ev + (size_t)i * 3;
+    if (!g_prof.ev) return CORR_OK;
+    for (int i = 0; i < g_prof.n; ++i) {
+        hipEvent_t* ev = g_prof.ev + (size_t)i * 3;
         if (hipEventSynchronize(ev[2]) != hipSuccess) return CORR_ERR_HIP;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ev[0], ev[1]) != hipSuccess) return CORR_ERR_HIP;
@@ -364,9 +385,71 @@ corr_status corr_profile_read(corr_pyramid* pyr, corr_profile* prof) {
         if (hipEventElapsedTime(&ms, ev[1], ev[2]) != hipSuccess) return CORR_ERR_HIP;
         prof->block_ms += ms;
     }
-    prof->lookups = pyr->prof_n;
-    pyr->prof_n = 0;
+    prof->lookups = g_prof.n;
+    prof->dropped = g_prof.dropped;
+    g_prof.n = 0;
+    g_prof.dropped = 0;
     return CORR_OK;
+}
+
+corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32_t* items, size_t items_cap,
+                                 int32_t* perm, size_t perm_cap, void* stream) {
+    if (!pyr || !counts || !items || !perm) return CORR_ERR_INVALID_ARG;
+    if (!pyr->ws_mem) return CORR_ERR_MISSING_REP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int hn[4];
+    if (hipMemcpyAsync(hn, pyr->ws.n_items, sizeof(hn), hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return CORR_ERR_HIP;
+    counts[0] = hn[0]; counts[1] = hn[1];
+    if ((size_t)hn[0] > items_cap || (size_t)hn[1] > perm_cap) return CORR_ERR_INVALID_ARG;
+    if (hn[0] > 0 && hipMemcpyAsync(items, pyr->ws.items, (size_t)hn[0] * 16, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return CORR_ERR_HIP;
+    if (hn[1] > 0 && hipMemcpyAsync(perm, pyr->ws.perm, (size_t)hn[1] * 4, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return CORR_ERR_HIP;
+    return hipStreamSynchronize(s) == hipSuccess ? CORR_OK : CORR_ERR_HIP;
+}
+
+corr_status corr_debug_cell_coords(const corr_pyramid* pyr, int cell_id, int* b, int* u, int* v) {
+    if (!pyr || !b || !u || !v || cell_id < 0 || cell_id >= corr_ncells(pyr->grid, pyr->B)) return CORR_ERR_INVALID_ARG;
+    corr_cell_coords(pyr->grid, cell_id, b, u, v);
+    *u += pyr->grid.u_min; *v += pyr->grid.v_min;
+    return CORR_OK;
+}
+
+corr_status corr_debug_read_level(const corr_pyramid* pyr, unsigned rep, int level, float* dst, void* stream) {
+    if (!pyr || !dst || level < -1 || level >= pyr->L) return CORR_ERR_INVALID_ARG;
+    if (rep != CORR_REP_F32 && rep != CORR_REP_SPLIT && rep != CORR_REP_BF16) return CORR_ERR_INVALID_ARG;
+    if (!(pyr->built & rep)) return CORR_ERR_MISSING_REP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int D = pyr->D, NC = D / CORR_CHUNK;
+    const size_t npix = level < 0 ? (size_t)pyr->B * pyr->H * pyr->W : (size_t)pyr->B * pyr->Hl[level] * pyr->Wl[level];
+    if (rep == CORR_REP_F32) {
+        const float* src = level < 0 ? pyr->f1_nhwc : pyr->f2_nhwc[level];
+        if (hipMemcpyAsync(dst, src, npix * D * 4, hipMemcpyDeviceToHost, s) != hipSuccess) return CORR_ERR_HIP;
+        return hipStreamSynchronize(s) == hipSuccess ? CORR_OK : CORR_ERR_HIP;
+    }
+    // chunk planes of [pixel][rec] bf16 records: rec = 64 (32 hi, 32 lo) or 32 (hi)
+    const int rec = rep == CORR_REP_SPLIT ? 64 : 32;
+    const uint16_t* base = rep == CORR_REP_SPLIT ? (level < 0 ? pyr->f1_split : pyr->f2_split)
+                                                 : (level < 0 ? pyr->f1_hi : pyr->f2_hi);
+    const size_t plane = level < 0 ? (size_t)pyr->B * pyr->H * pyr->W : (size_t)pyr->f2_pix_total;
+    const size_t first = level < 0 ? 0 : (size_t)pyr->f2_pix_base[level];
+    uint16_t* tmp = static_cast<uint16_t*>(malloc(npix * rec * 2));
+    if (!tmp) return CORR_ERR_OOM;
+    corr_status st = CORR_OK;
+    for (int kc = 0; kc < NC && st == CORR_OK; ++kc) {
+        if (hipMemcpyAsync(tmp, base + ((size_t)kc * plane + first) * rec, npix * rec * 2, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess) { st = CORR_ERR_HIP; break; }
+        for (size_t p = 0; p < npix; ++p)
+            for (int k = 0; k < CORR_CHUNK; ++k) {
+                uint32_t hb = (uint32_t)tmp[p * rec + k] << 16, lb = rec == 64 ? (uint32_t)tmp[p * rec + 32 + k] << 16 : 0u;
+                float hf, lf;
+                memcpy(&hf, &hb, 4); memcpy(&lf, &lb, 4);
+                dst[p * D + kc * CORR_CHUNK + k] = hf + lf;
+            }
+    }
+    free(tmp);
+    return st;
 }
 
 }  // extern "C"

@@ -4,19 +4,21 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "corr.h"
+#include "corr_bench.h"
 
 #define CORR_MAX_L 4
 #define CORR_CHUNK 32          // channels per chunk plane of the split representation
-#define CORR_GROUP 64          // queries per work item
+#define CORR_GROUP 128         // queries per work item (four waves of 32)
 #define CORR_BLOCK_MAX_D 256   // channels of query fragments a wave of the block kernel holds in registers at a time
 #define CORR_R 4               // largest lookup radius; the cell grid is laid out for it
-#ifndef CORR_LOG_CX
-#define CORR_LOG_CX 3          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
-#endif
+#define CORR_LOG_CX 4          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
 #define CORR_LOG_CY 3
+#define CORR_SUB (1 << CORR_LOG_CY)   // sub-bins per cell: one per target row, so a cell's queries come sorted by row
+#define CORR_LOG_TX 2          // super-tile: 2^LOG_TX x 2^LOG_TY cells whose ids are consecutive
+#define CORR_LOG_TY 3
+#define CORR_TILE_CELLS (1 << (CORR_LOG_TX + CORR_LOG_TY))
 #define CORR_COORD_LIMIT 1048576.0f
 #define CORR_NSTATS 24
-#define CORR_PROF_LOOKUPS 256
 
 // Target-cell grid.  A query belongs to the cell (floor(cx) >> LOG_CX,
 // floor(cy) >> LOG_CY).  Because floor(c / 2^l) == floor(c) >> l, all queries of
@@ -24,25 +26,39 @@
 // max(CX >> l, 1) x max(CY >> l, 1) level-l pixels, so one fixed window per
 // level serves the whole cell.
 struct CellGrid {
-    int log_cx, log_cy;
     int u_min, v_min;      // cell coordinates of grid entry (0, 0); may be negative
     int nbx, nby;          // cells per axis (covers every query that is in range at some level)
-    int tnx, tny;          // 8x8-cell super-tiles per axis (grid padded up)
-    int r;
+    int tnx, tny;          // super-tiles per axis (grid padded up)
 };
 
-// Cell ids are super-tile major: the 64 cells of an 8x8 super-tile are consecutive, so work items
-// that run at the same time on one XCD cover a compact 2-D patch of the target image and find
-// each other's window rows and columns in that XCD's L2.
+// Cell ids are super-tile major: the cells of a 4 x 8 super-tile (64 x 64 target pixels) are
+// consecutive, so work items that run at the same time on one XCD cover a compact 2-D patch of
+// the target image and find each other's window rows and columns in that XCD's L2.
 __host__ __device__ static inline int corr_cell_id(const CellGrid& g, int b, int u, int v) {   // u, v grid-relative
-    return (((b * g.tny + (v >> 3)) * g.tnx + (u >> 3)) << 6) + ((v & 7) << 3) + (u & 7);
+    return (((b * g.tny + (v >> CORR_LOG_TY)) * g.tnx + (u >> CORR_LOG_TX)) << (CORR_LOG_TX + CORR_LOG_TY)) +
+           ((v & ((1 << CORR_LOG_TY) - 1)) << CORR_LOG_TX) + (u & ((1 << CORR_LOG_TX) - 1));
 }
 __host__ __device__ static inline void corr_cell_coords(const CellGrid& g, int id, int* b, int* u, int* v) {
-    const int tile = id >> 6, in = id & 63;
-    *u = (tile % g.tnx) * 8 + (in & 7);
-    *v = ((tile / g.tnx) % g.tny) * 8 + (in >> 3);
+    const int tile = id >> (CORR_LOG_TX + CORR_LOG_TY), in = id & (CORR_TILE_CELLS - 1);
+    *u = ((tile % g.tnx) << CORR_LOG_TX) + (in & ((1 << CORR_LOG_TX) - 1));
+    *v = (((tile / g.tnx) % g.tny) << CORR_LOG_TY) + (in >> CORR_LOG_TX);
     *b = tile / (g.tnx * g.tny);
 }
+
+// Per-lookup planning workspace (device memory).  Sized by corr_ws_layout().
+struct BinWs {
+    int* bin_count;                // [nbins] zero between calls; bin = cell * CORR_SUB + (target row & (CORR_SUB - 1))
+    int* bin_off;                  // [nbins] exclusive prefix of counts
+    int* q_bin;                    // [B*H*W] bin id or -1
+    int* q_rank;                   // [B*H*W] slot within the bin
+    int* perm;                     // [B*H*W] queries sorted by bin
+    int4* items;                   // [max_items] {cell id, first perm index, n queries, 0}
+    int* n_items;                  // [4]: items, binned queries, count-kernel tickets, 0
+    long long* stats;              // [CORR_NSTATS]: 8+4*l+{0,1,2,3} per level
+    int ncells, nbins, max_items;
+};
+// Byte offsets of the workspace arrays inside one allocation of `total` bytes.
+struct WsLayout { size_t bin_count, bin_off, q_bin, q_rank, perm, items, n_items, stats, total; };
 
 struct corr_pyramid {
     int B, H, W, D, L;
@@ -50,8 +66,6 @@ struct corr_pyramid {
     unsigned built;                // representations that hold the current pair (set by each build)
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     CellGrid grid;
-    int nbins;                     // B * 64 * tnx * tny
-    int max_items;
     // CORR_REP_F32: channels-last fp32
     float* f1_nhwc;                // [B][H*W][D]
     float* f2_nhwc[CORR_MAX_L];    // [B][H_l*W_l][D]
@@ -64,57 +78,86 @@ struct corr_pyramid {
     uint16_t* f2_hi;
     int f2_pix_base[CORR_MAX_L];   // first pixel of level l in a chunk plane
     int f2_pix_total;              // pixels per chunk plane
-    // block-mode workspace
-    int* bin_count;                // [nbins] zero between calls
-    int* bin_off;                  // [nbins] exclusive prefix of counts
-    int* q_bin;                    // [B*H*W] cell id or -1
-    int* q_rank;                   // [B*H*W] slot within the cell
-    int* perm;                     // [B*H*W] queries sorted by cell
-    int4* items;                   // [max_items] {cell id, first perm index, n queries, 0}
-    int* n_items;                  // [4]: items, binned queries
-    long long* stats;              // [CORR_NSTATS]: 0..4 totals, 8+4*l+{0,1,2,3} per level
-    // CORR_MODE_FULLVOLUME cache
+    // block-mode workspace (one allocation, carved by corr_ws_layout)
+    void* ws_mem;
+    BinWs ws;
+    // CORR_MODE_FULLVOLUME cache (built lazily by the first full-volume lookup after a build)
     float* vol[CORR_MAX_L];        // [B][H*W][H_l*W_l]
     int vol_valid;
     size_t bytes;
-    int out_nhwc;                  // layout of `out` for the call being enqueued (set by corr_sample_layout)
-    int last_r;                    // radius of the last block-mode lookup (for its work counters)
-    // timing hook
-    int prof_on, prof_n;
-    hipEvent_t* prof_ev;           // [CORR_PROF_LOOKUPS][3]
 };
 
-// Fills `g` for level sizes (H >> l, W >> l), l < L, and radius r.
-static inline void corr_fill_grid(CellGrid* g, int H, int W, int L, int r) {
-    g->log_cx = CORR_LOG_CX; g->log_cy = CORR_LOG_CY; g->r = r;
+// Fills `g` for level sizes (H >> l, W >> l), l < L, and the largest radius.
+static inline void corr_fill_grid(CellGrid* g, int H, int W, int L) {
+    const int r = CORR_R;
     const int m = L - 1;                       // the coarsest level reaches furthest outside
     // in range at level m  <=>  floor(c) >> m in [-r-1, W_m + r - 1]
     const int lo_x = (-r - 1) * (1 << m), hi_x = ((W >> m) + r) * (1 << m) - 1;
     const int lo_y = (-r - 1) * (1 << m), hi_y = ((H >> m) + r) * (1 << m) - 1;
-    g->u_min = lo_x >> g->log_cx;              // arithmetic shift = floor
-    g->v_min = lo_y >> g->log_cy;
-    g->nbx = (hi_x >> g->log_cx) - g->u_min + 1;
-    g->nby = (hi_y >> g->log_cy) - g->v_min + 1;
-    g->tnx = (g->nbx + 7) >> 3;
-    g->tny = (g->nby + 7) >> 3;
+    g->u_min = lo_x >> CORR_LOG_CX;            // arithmetic shift = floor
+    g->v_min = lo_y >> CORR_LOG_CY;
+    g->nbx = (hi_x >> CORR_LOG_CX) - g->u_min + 1;
+    g->nby = (hi_y >> CORR_LOG_CY) - g->v_min + 1;
+    g->tnx = (g->nbx + (1 << CORR_LOG_TX) - 1) >> CORR_LOG_TX;
+    g->tny = (g->nby + (1 << CORR_LOG_TY) - 1) >> CORR_LOG_TY;
+}
+static inline int corr_ncells(const CellGrid& g, int B) { return B * CORR_TILE_CELLS * g.tnx * g.tny; }
+static inline int corr_max_items(int BN, int ncells) { return BN / CORR_GROUP + (ncells < BN ? ncells : BN) + 1; }
+static inline WsLayout corr_ws_layout(int BN, int ncells) {
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    WsLayout w;
+    const size_t nbins = (size_t)ncells * CORR_SUB;
+    size_t o = 0;
+    w.bin_count = o; o = up(o + nbins * 4);
+    w.bin_off = o; o = up(o + nbins * 4);
+    w.q_bin = o; o = up(o + (size_t)BN * 4);
+    w.q_rank = o; o = up(o + (size_t)BN * 4);
+    w.perm = o; o = up(o + (size_t)BN * 4);
+    w.items = o; o = up(o + (size_t)corr_max_items(BN, ncells) * 16);
+    w.n_items = o; o = up(o + 16);
+    w.stats = o; o = up(o + CORR_NSTATS * 8);
+    w.total = o;
+    return w;
+}
+static inline BinWs corr_ws_carve(void* mem, int BN, int ncells) {
+    const WsLayout w = corr_ws_layout(BN, ncells);
+    char* m = static_cast<char*>(mem);
+    BinWs s;
+    s.bin_count = reinterpret_cast<int*>(m + w.bin_count); s.bin_off = reinterpret_cast<int*>(m + w.bin_off);
+    s.q_bin = reinterpret_cast<int*>(m + w.q_bin); s.q_rank = reinterpret_cast<int*>(m + w.q_rank);
+    s.perm = reinterpret_cast<int*>(m + w.perm); s.items = reinterpret_cast<int4*>(m + w.items);
+    s.n_items = reinterpret_cast<int*>(m + w.n_items); s.stats = reinterpret_cast<long long*>(m + w.stats);
+    s.ncells = ncells; s.nbins = ncells * CORR_SUB; s.max_items = corr_max_items(BN, ncells);
+    return s;
 }
 
+// What one lookup call asks for beyond the pyramid: passed down to the launchers, never stored.
+struct LookupArgs {
+    const float* coords;
+    float* out;
+    int r;          // radius of this lookup
+    int nhwc;       // layout of out
+    int prec;       // corr_precision
+};
 // Where tap t of pixel p of batch item b goes in `out`: b * taps * HW + t * tap_stride + p * pix_stride,
 // with (tap_stride, pix_stride) = (HW, 1) for NCHW and (1, taps) for NHWC.
-static inline int corr_tap_stride(const corr_pyramid* p) { return p->out_nhwc ? 1 : p->H * p->W; }
-static inline int corr_pix_stride(const corr_pyramid* p, int r) { return p->out_nhwc ? p->L * (2 * r + 1) * (2 * r + 1) : 1; }
+static inline int corr_tap_stride(const corr_pyramid* p, const LookupArgs& q) { return q.nhwc ? 1 : p->H * p->W; }
+static inline int corr_pix_stride(const corr_pyramid* p, const LookupArgs& q) {
+    return q.nhwc ? p->L * (2 * q.r + 1) * (2 * q.r + 1) : 1;
+}
 
 // launchers (each enqueues on `s` and returns hipGetLastError())
 hipError_t launch_build_features(const float* nchw, int B, int D, int H, int W, int nlev,
                                  uint16_t* split, uint16_t* hi, float* const* nhwc, hipStream_t s);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s);
-hipError_t launch_binning(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
-hipError_t launch_bin_stats(corr_pyramid* p, hipStream_t s);
+hipError_t launch_fill_i32(int* dst, int value, size_t n, hipStream_t s);
+hipError_t launch_binning(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s);
+hipError_t launch_bin_stats(const corr_pyramid* p, const BinWs& ws, int r, hipStream_t s);
 // one instantiation of block.hip per lookup radius
-hipError_t launch_block_r1(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
-hipError_t launch_block_r2(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
-hipError_t launch_block_r3(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
-hipError_t launch_block_r4(corr_pyramid* p, const float* coords, int prec, float* out, hipStream_t s);
-hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
-hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s);
-hipError_t launch_fullvol_sample(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s);
+hipError_t launch_block_r1(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s);
+hipError_t launch_block_r2(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s);
+hipError_t launch_block_r3(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s);
+hipError_t launch_block_r4(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s);
+hipError_t launch_ondemand(const corr_pyramid* p, const LookupArgs& q, hipStream_t s);
+hipError_t launch_fullvol_build(const corr_pyramid* p, hipStream_t s);
+hipError_t launch_fullvol_sample(const corr_pyramid* p, const LookupArgs& q, hipStream_t s);

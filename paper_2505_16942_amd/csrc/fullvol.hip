@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void vol_sample_kernel(FvArgs a) {
 
 }  // namespace
 
-hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s) {
+hipError_t launch_fullvol_build(const corr_pyramid* p, hipStream_t s) {
     const int N = p->H * p->W;
     dim3 grid((N + 63) / 64, (N + 63) / 64, p->B);
     hipLaunchKernelGGL(vol_gemm_kernel, grid, dim3(256), 0, s, p->f1_nhwc, p->f2_nhwc[0], p->vol[0], N, p->D,
@@ -115,15 +115,15 @@ hipError_t launch_fullvol_build(corr_pyramid* p, hipStream_t s) {
     return hipSuccess;
 }
 
-hipError_t launch_fullvol_sample(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s) {
+hipError_t launch_fullvol_sample(const corr_pyramid* p, const LookupArgs& q, hipStream_t s) {
     FvArgs a;
     for (int l = 0; l < CORR_MAX_L; ++l) {
         a.vol[l] = l < p->L ? p->vol[l] : nullptr;
         a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
     }
-    a.coords = coords; a.out = out; a.B = p->B; a.HW = p->H * p->W; a.L = p->L; a.r = r;
-    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, r);
-    const int K = 2 * r + 1;
+    a.coords = q.coords; a.out = q.out; a.B = p->B; a.HW = p->H * p->W; a.L = p->L; a.r = q.r;
+    a.tap_stride = corr_tap_stride(p, q); a.pix_stride = corr_pix_stride(p, q);
+    const int K = 2 * q.r + 1;
     const size_t total = (size_t)p->B * p->L * K * K * a.HW;
     hipLaunchKernelGGL(vol_sample_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
     return hipGetLastError();

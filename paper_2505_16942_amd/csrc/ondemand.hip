@@ -97,11 +97,11 @@ __global__ __launch_bounds__(256) void ondemand_kernel(OdArgs a) {
 
 }  // namespace
 
-hipError_t launch_ondemand(corr_pyramid* p, const float* coords, int r, float* out, hipStream_t s) {
+hipError_t launch_ondemand(const corr_pyramid* p, const LookupArgs& q, hipStream_t s) {
     OdArgs a;
-    a.f1 = p->f1_nhwc; a.coords = coords; a.out = out;
-    a.B = p->B; a.HW = p->H * p->W; a.D = p->D; a.L = p->L; a.r = r;
-    a.tap_stride = corr_tap_stride(p); a.pix_stride = corr_pix_stride(p, r);
+    a.f1 = p->f1_nhwc; a.coords = q.coords; a.out = q.out;
+    a.B = p->B; a.HW = p->H * p->W; a.D = p->D; a.L = p->L; a.r = q.r;
+    a.tap_stride = corr_tap_stride(p, q); a.pix_stride = corr_pix_stride(p, q);
     for (int l = 0; l < CORR_MAX_L; ++l) {
         a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr;
         a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];

@@ -1,5 +1,5 @@
-"""The C-ABI library loads and exports every symbol include/corr.h declares; host-only entry
-points behave as documented.  No device work here."""
+"""The C-ABI library loads and exports every symbol include/corr.h and include/corr_bench.h
+declare; host-only entry points behave as documented.  No device work here."""
 import ctypes
 import os
 import re
@@ -8,10 +8,11 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "corr.h")
+BENCH_HEADER = os.path.join(ROOT, "include", "corr_bench.h")
 
 
-def _declared_functions():
-    src = open(HEADER).read()
+def _declared_functions(header=HEADER):
+    src = open(header).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = re.findall(r"\b(corr_[a-z0-9_]+)\s*\(", src)
     return sorted(set(names))
@@ -31,6 +32,11 @@ def test_header_symbols_are_exported():
     for name in declared:
         assert hasattr(lib, name), "missing export: " + name
     assert sorted(binding.EXPORTS) == declared
+    hooks = _declared_functions(BENCH_HEADER)
+    assert "corr_copy_f32" in hooks and not set(hooks) & set(declared)
+    for name in hooks:
+        assert hasattr(lib, name), "missing export: " + name
+    assert sorted(binding.BENCH_EXPORTS) == hooks
 
 
 def test_full_volume_bytes_matches_closed_form():
@@ -48,10 +54,16 @@ def test_status_strings_and_workspace():
     binding, _ = _lib()
     seen = {binding.status_string(s) for s in (0, -1, -2, -3, -4, -5)}
     assert len(seen) == 6 and "ok" in seen
-    ws = binding.corr_workspace_bytes(binding.CORR_REP_SPLIT, 1, 540, 960, 256, 4)
     feat = 4 * 256 * (540 * 960 + sum((540 >> l) * (960 >> l) for l in range(4)))
-    assert feat < ws < feat * 1.02          # workspace beyond the features is linear in pixels and small
-    assert binding.corr_workspace_bytes(1, 1, 16, 16, 48, 2) == 0   # unsupported D
+    ws = binding.corr_workspace_bytes(binding.CORR_MODE_BLOCK, 1, 540, 960, 256, 4, 4)
+    assert feat < ws < feat * 1.02          # workspace beyond the features is linear in pixels and small (Eq. 4)
+    assert binding.corr_workspace_bytes(binding.CORR_MODE_ONDEMAND, 1, 540, 960, 256, 4, 4) == feat
+    assert binding.corr_workspace_bytes(binding.CORR_MODE_FULLVOLUME, 1, 540, 960, 256, 4, 4) == feat + 1427549184000
+    # linear in the number of pixels: four times the pixels, about four times the bytes
+    small = binding.corr_workspace_bytes(binding.CORR_MODE_BLOCK, 1, 270, 480, 256, 4, 4)
+    assert 3.9 < ws / small < 4.1
+    assert binding.corr_workspace_bytes(binding.CORR_MODE_BLOCK, 1, 16, 16, 48, 2, 4) == 0   # unsupported D
+    assert binding.corr_workspace_bytes(binding.CORR_MODE_BLOCK, 1, 16, 16, 64, 2, 5) == 0   # unsupported r
 
 
 def test_bin_geometry_matches_the_rule():
@@ -59,11 +71,10 @@ def test_bin_geometry_matches_the_rule():
     for (H, W, L) in [(540, 960, 4), (46, 62, 4), (16, 24, 2), (9, 9, 1)]:
         for l in range(L):
             cx, cy, wx, wy, nx, ny = binding.corr_bin_geometry(H, W, L, l)
-            assert cx == max(8 >> l, 1) and cy == max(8 >> l, 1)
+            assert cx == max(16 >> l, 1) and cy == max(8 >> l, 1)
             assert wx == cx + 9 and wy == cy + 9
             m = L - 1
-            lo = (-5 * (1 << m)) >> 3
-            assert nx == ((((W >> m) + 4) * (1 << m) - 1) >> 3) - lo + 1
-            assert ny == ((((H >> m) + 4) * (1 << m) - 1) >> 3) - lo + 1
+            assert nx == ((((W >> m) + 4) * (1 << m) - 1) >> 4) - ((-5 * (1 << m)) >> 4) + 1
+            assert ny == ((((H >> m) + 4) * (1 << m) - 1) >> 3) - ((-5 * (1 << m)) >> 3) + 1
     with pytest.raises(binding.CorrError):
         binding.corr_bin_geometry(4, 4, 4, 0)

@@ -35,7 +35,7 @@ def _run(f1, f2, c, L, r, mode, prec=0, reps=3):
     b.corr_sample(t1, pyr, tc, r=r, out=out, mode=mode, prec=prec)
     torch.cuda.synchronize()
     res = out.cpu().numpy()
-    stats = b.corr_last_block_stats(pyr) if mode == b.CORR_MODE_BLOCK else None
+    stats = b.corr_last_block_stats(pyr, r) if mode == b.CORR_MODE_BLOCK else None
     pyr.destroy()
     return res, stats
 
@@ -95,15 +95,19 @@ def test_feature_maps_not_16_byte_aligned():
     pyr.destroy()
 
 
-@pytest.mark.parametrize("reps", [1, 2, 3, 4, 5, 7])
-def test_pyramid_bytes_equal_the_host_estimate(reps):
-    """corr_workspace_bytes (host arithmetic) is what a pyramid with those representations holds."""
+@pytest.mark.parametrize("mode,reps", [(0, 1), (1, 2)])
+def test_pyramid_bytes_equal_the_host_estimate(mode, reps):
+    """corr_workspace_bytes (host arithmetic) is what a pyramid built for that mode holds."""
     b = _binding()
     dev = torch.device("cuda:0")
     B, H, W, D, L = 2, 37, 53, 96, 3
     f = torch.zeros((B, D, H, W), device=dev)
     pyr = b.corr_pyramid_build(f, f, L=L, reps=reps)
-    assert pyr.bytes() == b.corr_workspace_bytes(reps, B, H, W, D, L)
+    assert pyr.bytes() == b.corr_workspace_bytes(mode, B, H, W, D, L, 4)
+    if mode == 1:      # the dense volume appears with the first full-volume lookup
+        c = torch.zeros((B, 2, H, W), device=dev)
+        b.corr_sample(f, pyr, c, mode=b.CORR_MODE_FULLVOLUME)
+        assert pyr.bytes() == b.corr_workspace_bytes(b.CORR_MODE_FULLVOLUME, B, H, W, D, L, 4)
     pyr.destroy()
 
 
@@ -122,7 +126,7 @@ def test_bf16_only_representation():
     with pytest.raises(b.CorrError) as e:
         b.corr_sample(t1, p_hi, tc)                                   # bf16x3 needs the lo parts
     assert e.value.status == b.CORR_ERR_MISSING_REP
-    assert p_hi.bytes() < b.corr_workspace_bytes(b.CORR_REP_SPLIT, B, H, W, D, L)
+    assert p_hi.bytes() < b.corr_workspace_bytes(b.CORR_MODE_BLOCK, B, H, W, D, L, 4)
     p_sp = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_SPLIT)
     got_sp = b.corr_sample(t1, p_sp, tc, prec=b.CORR_PREC_BF16)
     assert torch.equal(got_hi, got_sp)
@@ -216,7 +220,7 @@ def test_other_radii(r, mode):
 
 @pytest.mark.parametrize("r", [1, 2, 3])
 def test_other_radii_block_mode_four_levels_far_motion_and_layouts(r):
-    """Block mode at r < 4: four levels (fused coarse pass), windows partly outside, null queries,
+    """Block mode at r < 4: four levels, windows partly outside, null queries,
     bf16 mode and the channels-last layout."""
     b = _binding()
     dev = torch.device("cuda:0")
@@ -230,7 +234,7 @@ def test_other_radii_block_mode_four_levels_far_motion_and_layouts(r):
     out = torch.full((B, L * K * K, H, W), float("nan"), dtype=torch.float32, device=dev)
     b.corr_sample(t1, pyr, tc, r=r, out=out)
     _check(out.cpu().numpy(), ref, FP32_TOL, "block r=%d" % r)
-    stats = b.corr_last_block_stats(pyr)
+    stats = b.corr_last_block_stats(pyr, r)
     assert stats["query_levels"] == B * H * W * L and 0 < stats["null_query_levels"] < B * H * W * L
     o16 = b.corr_sample(t1, pyr, tc, r=r, prec=b.CORR_PREC_BF16)
     _check(o16.cpu().numpy(), ref, BF16_TOL, "block bf16 r=%d" % r)
