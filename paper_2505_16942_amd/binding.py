@@ -16,6 +16,8 @@ LIB_PATH = os.path.join(_PKG, "libcorr_mi355x.so")
 
 CORR_OK = 0
 CORR_ERR_INVALID_ARG, CORR_ERR_UNSUPPORTED, CORR_ERR_OOM, CORR_ERR_HIP, CORR_ERR_MISSING_REP = -1, -2, -3, -4, -5
+CORR_ERR_TOO_LARGE = -6
+CORR_STATIC_SCRATCH_BYTES = 2 << 20
 CORR_MODE_BLOCK, CORR_MODE_ONDEMAND, CORR_MODE_FULLVOLUME = 0, 1, 2
 CORR_PREC_BF16X3, CORR_PREC_BF16 = 0, 1
 CORR_OUT_NCHW, CORR_OUT_NHWC = 0, 1
@@ -24,7 +26,7 @@ CORR_REP_SPLIT, CORR_REP_F32, CORR_REP_BF16 = 1, 2, 4
 # the method's boundary (include/corr.h)
 EXPORTS = [
     "corr_pyramid_build", "corr_pyramid_build_reps", "corr_pyramid_destroy", "corr_pyramid_bytes",
-    "corr_sample", "corr_sample_mode", "corr_sample_layout",
+    "corr_sample", "corr_sample_mode", "corr_sample_layout", "corr_sample_static",
     "corr_full_volume_bytes", "corr_workspace_bytes", "corr_status_string",
 ]
 # measurement and test hooks (include/corr_bench.h)
@@ -79,6 +81,8 @@ def load_library():
     lib.corr_sample_mode.restype = ci
     lib.corr_sample_layout.argtypes = [ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
     lib.corr_sample_layout.restype = ci
+    lib.corr_sample_static.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
+    lib.corr_sample_static.restype = ci
     lib.corr_full_volume_bytes.argtypes = [ci, ci, ci, ci]
     lib.corr_full_volume_bytes.restype = sz
     lib.corr_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci]
@@ -203,6 +207,29 @@ def corr_sample(fmap1, pyramid: Pyramid, coords: torch.Tensor, r: int = 4,
     st = lib.corr_sample_layout(mode, prec, layout, p1, pyramid.handle, pc, B, H, W, D, L, r, po, _stream())
     if st != CORR_OK:
         raise CorrError(st, "corr_sample")
+    return out
+
+
+def corr_sample_static(fmap1, pyramid: Pyramid, coords: torch.Tensor, r: int = 4,
+                       out: torch.Tensor | None = None) -> torch.Tensor:
+    """corr_sample (block mode, bf16x3, NCHW) on the library's fixed planning scratch: allocates nothing
+    inside the library.  Raises CorrError(CORR_ERR_TOO_LARGE) beyond the scratch size."""
+    lib = load_library()
+    pc = _dev_f32(coords, "coords")
+    B, H, W, D, L = pyramid.B, pyramid.H, pyramid.W, pyramid.D, pyramid.L
+    if tuple(coords.shape) != (B, 2, H, W):
+        raise ValueError("coords must be [B, 2, H, W] = %s" % ((B, 2, H, W),))
+    K = 2 * r + 1
+    shape = (B, L * K * K, H, W)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=coords.device)
+    elif tuple(out.shape) != shape:
+        raise ValueError("out has the wrong shape")
+    po = _dev_f32(out, "out")
+    p1 = fmap1.data_ptr() if isinstance(fmap1, torch.Tensor) else None
+    st = lib.corr_sample_static(p1, pyramid.handle, pc, B, H, W, D, L, r, po, _stream())
+    if st != CORR_OK:
+        raise CorrError(st, "corr_sample_static")
     return out
 
 

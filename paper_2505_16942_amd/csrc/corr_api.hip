@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/corr.h: argument checks, the
 // pyramid object and its device allocations, and the order in which the kernels
 // of one build / one lookup are enqueued.
+#include <mutex>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -161,6 +162,32 @@ corr_status check_lookup_args(const corr_pyramid* pyr, const float* coords, cons
 
 }  // namespace
 
+// Planning workspace of corr_sample_static: one array per GPU, held until the process ends.  In
+// host code the symbol is only a handle; its device address comes from hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[CORR_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` on each GPU, looked up once
+
+corr_status static_scratch(void** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return CORR_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return CORR_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return CORR_OK;
+}
+}  // namespace
+
 extern "C" {
 
 const char* corr_status_string(corr_status s) {
@@ -171,6 +198,7 @@ const char* corr_status_string(corr_status s) {
         case CORR_ERR_OOM: return "out of device memory";
         case CORR_ERR_HIP: return "HIP error";
         case CORR_ERR_MISSING_REP: return "pyramid lacks the representation this mode reads";
+        case CORR_ERR_TOO_LARGE: return "input exceeds the fixed scratch buffer of corr_sample_static";
     }
     return "unknown status";
 }
@@ -320,6 +348,29 @@ corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_lay
 corr_status corr_sample(const float* fmap1, const corr_pyramid* pyr, const float* coords,
                         int B, int H, int W, int D, int L, int r, float* out, void* stream) {
     return corr_sample_mode(CORR_MODE_BLOCK, CORR_PREC_BF16X3, fmap1, pyr, coords, B, H, W, D, L, r, out, stream);
+}
+
+corr_status corr_sample_static(const float* fmap1, const corr_pyramid* pyr, const float* coords,
+                               int B, int H, int W, int D, int L, int r, float* out, void* stream) {
+    (void)fmap1;
+    corr_status st = check_lookup_args(pyr, coords, out, B, H, W, D, L, r);
+    if (st != CORR_OK) return st;
+    if (!(pyr->built & CORR_REP_SPLIT)) return CORR_ERR_MISSING_REP;
+    const int BN = B * H * W, ncells = corr_ncells(pyr->grid, B);
+    if (corr_ws_layout(BN, ncells).total > (size_t)CORR_STATIC_SCRATCH_BYTES) return CORR_ERR_TOO_LARGE;
+    void* mem = nullptr;
+    st = static_scratch(&mem);
+    if (st != CORR_OK) return st;
+    const BinWs ws = corr_ws_carve(mem, BN, ncells);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the array keeps the last call's contents, laid out for that call's sizes: the bin counters and
+    // the item / ticket counters must start at zero (fill kernels, so the call can be graph-captured)
+    hipError_t e = launch_fill_i32(ws.bin_count, 0, (size_t)ws.nbins, s);
+    if (e == hipSuccess) e = launch_fill_i32(ws.n_items, 0, 4, s);
+    LookupArgs q;
+    q.coords = coords; q.out = out; q.r = r; q.nhwc = 0; q.prec = (int)CORR_PREC_BF16X3;
+    if (e == hipSuccess) e = enqueue_block_lookup(pyr, ws, q, s);
+    return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 
 corr_status corr_last_block_stats(const corr_pyramid* pyr, int r, corr_block_stats* stats, void* stream) {

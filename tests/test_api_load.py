@@ -52,8 +52,8 @@ def test_full_volume_bytes_matches_closed_form():
 
 def test_status_strings_and_workspace():
     binding, _ = _lib()
-    seen = {binding.status_string(s) for s in (0, -1, -2, -3, -4, -5)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {binding.status_string(s) for s in (0, -1, -2, -3, -4, -5, -6)}
+    assert len(seen) == 7 and "ok" in seen
     feat = 4 * 256 * (540 * 960 + sum((540 >> l) * (960 >> l) for l in range(4)))
     ws = binding.corr_workspace_bytes(binding.CORR_MODE_BLOCK, 1, 540, 960, 256, 4, 4)
     assert feat < ws < feat * 1.02          # workspace beyond the features is linear in pixels and small (Eq. 4)
