@@ -71,7 +71,7 @@ corr_status corr_copy_f32(float* dst, const float* src, size_t n, void* stream);
  * to host buffers (synchronises `stream`).
  *   counts[2] : number of items, number of binned queries
  *   items     : up to items_cap entries of 4 ints {cell id, first index into perm, queries, 0}
- *   perm      : up to perm_cap entries: query indices b*H*W + y*W + x sorted by (cell, target row)
+ *   perm      : up to perm_cap entries: query indices b*H*W + y*W + x sorted by (cell, source row mod 8)
  * Returns CORR_ERR_INVALID_ARG if a buffer is too small for what the plan holds.
  */
 corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32_t* items, size_t items_cap,

@@ -13,12 +13,13 @@
 // for every level.  Queries out of range at every level are written as zeros
 // here and never reach the contraction.
 //
-// A counting sort over bins = (cell, target row within the cell), so that a
-// cell's queries come out sorted by target row:
+// A counting sort over bins = (cell, source row mod 8), so that a cell's queries
+// come out as runs of x-neighbouring source pixels, row after row: the lanes of
+// one store of the block kernel's epilogue then hit few cache lines.
 //   count   : bin id + slot per query (one atomic per run of equal bins among
 //             consecutive lanes); the workgroup that finishes last also runs
 //   scan    : cell and bin offsets, the item list
-//   scatter : queries sorted by bin.
+//   scatter : queries, and their coordinates, sorted by bin.
 // Small inputs run all three steps in one workgroup.
 #include "corr_internal.h"
 
@@ -30,7 +31,7 @@ constexpr int SMALL_MAX_Q = 8;        // queries per thread of the one-workgroup
 struct BinArgs {
     const float* coords;   // [B][2][H*W]
     float* out;            // [B][L*K*K][H*W]
-    int B, HW, L, r;              // r: radius of this lookup (the grid is laid out for the largest)
+    int B, HW, W, L, r;           // r: radius of this lookup (the grid is laid out for the largest)
     int tap_stride, pix_stride;   // layout of out
     CellGrid g;
     BinWs ws;
@@ -44,11 +45,10 @@ __device__ __forceinline__ int query_bin(const BinArgs& a, int b, int p) {
     const bool finite_ok = (fabsf(cx) <= CORR_COORD_LIMIT) && (fabsf(cy) <= CORR_COORD_LIMIT);
     int bin = -1;
     if (finite_ok) {
-        const int fy = (int)floorf(cy);
         const int u = ((int)floorf(cx) >> CORR_LOG_CX) - a.g.u_min;
-        const int v = (fy >> CORR_LOG_CY) - a.g.v_min;
+        const int v = ((int)floorf(cy) >> CORR_LOG_CY) - a.g.v_min;
         if (u >= 0 && u < a.g.nbx && v >= 0 && v < a.g.nby)
-            bin = corr_cell_id(a.g, b, u, v) * CORR_SUB + (fy & (CORR_SUB - 1));
+            bin = corr_cell_id(a.g, b, u, v) * CORR_SUB + ((p / a.W) & (CORR_SUB - 1));
     }
     if (bin < 0) {
         const int K = 2 * a.r + 1;
@@ -145,14 +145,16 @@ __global__ __launch_bounds__(SCAN_T) void bin_count_kernel(BinArgs a) {
     if (s_last) scan_cells(a.ws);
 }
 
-__global__ __launch_bounds__(256) void bin_scatter_kernel(const int* __restrict__ q_bin,
-                                                          const int* __restrict__ q_rank,
-                                                          const int* __restrict__ bin_off,
-                                                          int* __restrict__ perm, int BN) {
+__global__ __launch_bounds__(256) void bin_scatter_kernel(BinArgs a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= BN) return;
-    const int bin = q_bin[i];
-    if (bin >= 0) perm[bin_off[bin] + q_rank[i]] = i;
+    if (i >= a.B * a.HW) return;
+    const int bin = a.ws.q_bin[i];
+    if (bin >= 0) {
+        const int b = i / a.HW, p = i - b * a.HW;
+        const int pos = a.ws.bin_off[bin] + a.ws.q_rank[i];
+        a.ws.perm[pos] = i;
+        a.ws.sorted_c[pos] = make_float2(a.coords[((size_t)b * 2 + 0) * a.HW + p], a.coords[((size_t)b * 2 + 1) * a.HW + p]);
+    }
 }
 
 // Inputs of up to SCAN_T * SMALL_MAX_Q queries: count, scan and scatter in one workgroup, one launch.
@@ -172,7 +174,12 @@ __global__ __launch_bounds__(SCAN_T) void bin_small_kernel(BinArgs a) {
 #pragma unroll
     for (int k = 0; k < SMALL_MAX_Q; ++k) {
         const int q = k * SCAN_T + threadIdx.x;
-        if (q < BN && bin[k] >= 0) a.ws.perm[a.ws.bin_off[bin[k]] + rank[k]] = q;
+        if (q < BN && bin[k] >= 0) {
+            const int b = q / a.HW, p = q - b * a.HW;
+            const int pos = a.ws.bin_off[bin[k]] + rank[k];
+            a.ws.perm[pos] = q;
+            a.ws.sorted_c[pos] = make_float2(a.coords[((size_t)b * 2 + 0) * a.HW + p], a.coords[((size_t)b * 2 + 1) * a.HW + p]);
+        }
     }
 }
 
@@ -249,7 +256,7 @@ hipError_t launch_bin_stats(const corr_pyramid* p, const BinWs& ws, int r, hipSt
 hipError_t launch_binning(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s) {
     const int HW = p->H * p->W, BN = p->B * HW;
     BinArgs a;
-    a.coords = q.coords; a.out = q.out; a.B = p->B; a.HW = HW; a.L = p->L; a.r = q.r; a.g = p->grid;
+    a.coords = q.coords; a.out = q.out; a.B = p->B; a.HW = HW; a.W = p->W; a.L = p->L; a.r = q.r; a.g = p->grid;
     a.tap_stride = corr_tap_stride(p, q); a.pix_stride = corr_pix_stride(p, q);
     a.ws = ws;
     if (BN <= SCAN_T * SMALL_MAX_Q) {
@@ -259,7 +266,6 @@ hipError_t launch_binning(const corr_pyramid* p, const BinWs& ws, const LookupAr
     hipLaunchKernelGGL(bin_count_kernel, dim3((BN + SCAN_T - 1) / SCAN_T), dim3(SCAN_T), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bin_scatter_kernel, dim3((BN + 255) / 256), dim3(256), 0, s,
-                       ws.q_bin, ws.q_rank, ws.bin_off, ws.perm, BN);
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3((BN + 255) / 256), dim3(256), 0, s, a);
     return hipGetLastError();
 }

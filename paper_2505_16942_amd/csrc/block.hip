@@ -4,7 +4,8 @@
 //
 // One workgroup (4 waves, the only one on its CU) = one work item = (target cell of 16 x 8
 // level-0 pixels, up to 128 of its queries), processed level after level.  Wave w owns queries
-// 32w .. 32w+31 of the item as two MFMA column blocks of 16.
+// 16w .. 16w+15 and 64+16w .. 64+16w+15 of the item as two MFMA column blocks (items of up to 64
+// queries use one).
 //   queries     : each wave loads the bf16 hi (and lo) fragments of its queries for 256 channels
 //                 once per item, straight from global memory into the MFMA B-operand layout, and
 //                 keeps them in registers for all levels (a larger D runs in groups of 256 channels
@@ -49,20 +50,19 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int R = CORR_BLOCK_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 constexpr int NW = 4, NT = 64 * NW;
-constexpr int QW = CORR_GROUP / NW;                    // queries per wave: two column blocks of 16
 constexpr int XCD_RUN = 32;                            // consecutive items dealt to one XCD; a power of two
 constexpr int NCMAX = CORR_BLOCK_MAX_D / CORR_CHUNK;   // chunks of query fragments a wave holds
 constexpr int LDS_BYTES = 160 * 1024;
 constexpr int META_BYTES = CORR_GROUP * 12;
 constexpr int LDS_DATA = LDS_BYTES - META_BYTES;       // ring slots and S
 constexpr int OOB = (int)0x80000000u;                  // a buffer offset beyond the whole pyramid (< 2 GiB): loads zeros
-static_assert(QW == 32 && NW == 4, "a wave owns two 16-query column blocks");
+static_assert(CORR_GROUP == 128 && NW == 4, "a wave owns two 16-query column blocks");
 
 struct BlockArgs {
     const uint16_t* f1s;                 // [NC][B*HW][rec]
     const uint16_t* f2s;                 // [NC][P][rec], P = pixels of all levels; level l starts at pix_base[l]
-    const float* coords;                 // [B][2][HW]
-    const int* perm;
+    const int* perm;                     // queries sorted by (cell, source row mod 8)
+    const float2* sorted_c;              // their coordinates
     const int4* items;
     const int* n_items;
     float* out;
@@ -79,6 +79,12 @@ struct BlockArgs {
 #endif
 };
 
+// S rows are 64 queries + 4 floats of padding: the four row groups a wave writes at once then fall in
+// different banks, and a row read by 64 lanes still covers every bank once
+constexpr int SST = 68;
+#ifndef CORR_LDS_PF
+#define CORR_LDS_PF 3
+#endif
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 constexpr int cmin(int a, int b) { return a < b ? a : b; }
 
@@ -96,7 +102,7 @@ struct Geo {
     static constexpr int ITERS = (BPS * 16 * ROWB + 4095) / 4096;   // 16-byte loads per thread and unit
     static constexpr int SLOT = ITERS * 4096;             // LDS bytes of a ring slot
     static constexpr int NU = NCMAX * NG;                 // units per group of NCMAX chunks
-    static constexpr int S_BYTES = ROWS * 64 * 4;         // S of one epilogue round: [ROWS][64 queries] fp32
+    static constexpr int S_BYTES = ROWS * SST * 4;        // S of one epilogue round: [ROWS][64 queries] fp32
     // swizzle: the piece slot of a row is XORed with this, so that the 16 rows x 16 bytes a quarter
     // wave reads for one MFMA fragment fall in 16 different 4-bank groups
     __device__ static constexpr int swz(int r) { return PPR == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
@@ -110,13 +116,11 @@ struct Ring {
     static constexpr int UP = (LDS_DATA - SPREV) / G::SLOT;
     static constexpr int LOW = SPREV / G::SLOT;
     static constexpr int NS0 = cmin(G::NU, UP + LOW);
-    static constexpr int NS = NS0 / G::NG * G::NG;        // a slot always holds the same group of row blocks
+    static constexpr int NS = NS0;
     static constexpr int PRE = cmin(UP, NS);              // units that can be issued before the previous epilogue
-    static_assert(NS >= 2 && NS >= G::NG, "ring too small");
+    static_assert(NS >= 3, "ring too small");
     static_assert(G::S_BYTES <= LDS_DATA, "S does not fit");
     __device__ static constexpr int slot_off(int i) { return i < PRE ? SPREV + i * G::SLOT : (i - PRE) * G::SLOT; }
-    // loads that may still be in flight behind unit u when it is waited for
-    __device__ static constexpr int younger(int u) { return cmin(G::NU - 1, NS - 1 + cmax(u - 1, 0)) - u; }
 };
 
 #ifdef CORR_TRACE
@@ -132,10 +136,8 @@ struct ItemCtx {
     const int* q_pix;        // LDS: pixel of each query slot or -1
     const float* q_cx;       // LDS: raw coordinates
     const float* q_cy;
+    unsigned lds_base;       // LDS byte address of smem
     unsigned lds_wave;       // LDS byte address of smem + wave * 1024 (uniform)
-#ifdef CORR_DEBUG_SYNC_STAGE
-    unsigned char* dbg_smem;
-#endif
     i32x4 rsrc, rsrc_null;   // buffer resources: all chunk planes of f2s; an empty buffer
 };
 
@@ -189,10 +191,11 @@ __device__ __forceinline__ void plan(const BlockArgs& a, const ItemCtx& c, int (
         }
 }
 
-// issue the loads of unit u (chunk kc0 + u / NG, group u % NG) into its ring slot
+// issue loads it0 .. it1-1 of unit U (chunk kc0 + U / NG, group U % NG) into its ring slot
 template <int LVL, bool THREE, int U>
 __device__ __forceinline__ void issue_unit(const BlockArgs& a, const ItemCtx& c,
-                                           const int (&voff)[Geo<LVL, THREE>::NG][Geo<LVL, THREE>::ITERS], int kc0) {
+                                           const int (&voff)[Geo<LVL, THREE>::NG][Geo<LVL, THREE>::ITERS], int kc0,
+                                           int it0 = 0, int it1 = Geo<LVL, THREE>::ITERS) {
     using G = Geo<LVL, THREE>;
     using RG = Ring<LVL, THREE>;
     constexpr int g = U % G::NG, slot = U % RG::NS;
@@ -201,19 +204,13 @@ __device__ __forceinline__ void issue_unit(const BlockArgs& a, const ItemCtx& c,
     const i32x4 rs = real ? c.rsrc : c.rsrc_null;
     const unsigned soff = real ? (unsigned)kc * a.f2_plane_bytes : 0u;
 #pragma unroll
-    for (int it = 0; it < G::ITERS; ++it) {
-#ifdef CORR_DEBUG_SYNC_STAGE
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (real && voff[g][it] != OOB) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.f2s) + soff + voff[g][it]);
-        *reinterpret_cast<uint4*>(c.dbg_smem + RG::slot_off(slot) + (it * NT + c.tid) * 16) = v;
-#else
-        dma16(rs, c.lds_wave + RG::slot_off(slot) + it * 4096, voff[g][it], soff);
-#endif
-    }
+    for (int it = 0; it < G::ITERS; ++it)
+        if (it >= it0 && it < it1)                                // constants once the callers' loops are unrolled
+            dma16(rs, c.lds_wave + RG::slot_off(slot) + it * 4096, voff[g][it], soff);
 }
 
 // Query fragments of this wave for chunks kc0 .. kc0+NCMAX-1: lane holds channels 8*(lane/16) .. +7 of
-// every chunk of queries 32*wave + 16*h + lane%16 (the B operands of the MFMA).
+// every chunk of queries 64*h + 16*wave + lane%16, h = 0, 1 (the B operands of the MFMA).
 template <bool THREE>
 __device__ __forceinline__ void load_queries(const BlockArgs& a, const ItemCtx& c, int kc0,
                                              bf16x8 (&qhi)[2][NCMAX], bf16x8 (&qlo)[2][NCMAX]) {
@@ -221,7 +218,7 @@ __device__ __forceinline__ void load_queries(const BlockArgs& a, const ItemCtx& 
     const unsigned plane = (unsigned)a.f1_stride * 2u;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int pix = c.q_pix[c.wave * QW + h * 16 + (c.lane & 15)];
+        const int pix = c.q_pix[h * 64 + c.wave * 16 + (c.lane & 15)];
         const unsigned off = ((unsigned)(c.b * a.HW + max(pix, 0)) * (unsigned)a.rec + (unsigned)(c.lane >> 4) * 8u) * 2u;
 #pragma unroll
         for (int kk = 0; kk < NCMAX; ++kk) {
@@ -241,74 +238,109 @@ __device__ __forceinline__ void load_queries(const BlockArgs& a, const ItemCtx& 
     __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0), expcnt and lgkmcnt untouched
 }
 
-// the MFMAs of unit U: every row block of its group against this wave's two query column blocks.
-// The fragment reads run two row blocks ahead of the MFMAs that use them; sched_group_barrier
-// pins that order (left alone, the scheduler hoists every read of the unit and spills).
-template <int LVL, bool THREE, int U>
-__device__ __forceinline__ void mfma_unit(const ItemCtx& c, const unsigned char* smem,
-                                          const bf16x8 (&qhi)[2][NCMAX], const bf16x8 (&qlo)[2][NCMAX],
-                                          f32x4 (&acc)[Geo<LVL, THREE>::NB][2], int frag_hi, int frag_lo) {
+// The chunk loop of one level over NCMAX chunks starting at kc0, software-pipelined across units.
+// Units 0 .. pre-1 were issued by the caller (before the previous level's epilogue); the rest of
+// the ring is filled here.  Step U multiplies the row blocks of unit U with this wave's query
+// column blocks.  Half way through it the wave waits for unit U + 1 and meets the others at the one
+// barrier of the step (so everyone is also done with unit U - 1, whose slot is then refilled with
+// unit U - 1 + NS, a few loads at a time between the row blocks), and its last row blocks already
+// read the first fragments of unit U + 1: the matrix pipe never waits for a barrier or for the
+// first LDS reads of a unit.  There is no branch in the loop: a wave without queries, or a chunk past
+// the last one (loaded as zeros), multiplies anyway; a branch here makes the compiler move every
+// accumulator between register files around it.  The fragment reads run PF row blocks ahead of their
+// MFMAs; a sched_barrier after every row block pins that distance (left alone, the scheduler sinks each
+// read to just before its use, or hoists them all and spills).
+template <int LVL, bool THREE, bool TWO>
+struct KLoop {
     using G = Geo<LVL, THREE>;
     using RG = Ring<LVL, THREE>;
-    constexpr int g = U % G::NG, slot = U % RG::NS, kc = U / G::NG;
-    constexpr int NJ = (G::NB - g + G::NG - 1) / G::NG;      // row blocks of this group
-    constexpr int PF = 2;
-    const unsigned char* rows = smem + RG::slot_off(slot);
-    bf16x8 wh[NJ + PF], wl[NJ + PF];
-#pragma unroll
-    for (int j = 0; j < PF; ++j) {
-        if (j < NJ) {
-            wh[j] = *reinterpret_cast<const bf16x8*>(rows + j * 16 * G::ROWB + frag_hi);
-            if (THREE) wl[j] = *reinterpret_cast<const bf16x8*>(rows + j * 16 * G::ROWB + frag_lo);
-        }
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, (THREE ? 2 : 1) * cmin(PF, NJ), 0);
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        const int b = j * G::NG + g;
-        if (j + PF < NJ) {
-            wh[j + PF] = *reinterpret_cast<const bf16x8*>(rows + (j + PF) * 16 * G::ROWB + frag_hi);
-            if (THREE) wl[j + PF] = *reinterpret_cast<const bf16x8*>(rows + (j + PF) * 16 * G::ROWB + frag_lo);
-        }
-        if (THREE) {
-            acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[j], qhi[0][kc], acc[b][0], 0, 0, 0);
-            acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[j], qhi[1][kc], acc[b][1], 0, 0, 0);
-            acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qlo[0][kc], acc[b][0], 0, 0, 0);
-            acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qlo[1][kc], acc[b][1], 0, 0, 0);
-        }
-        acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qhi[0][kc], acc[b][0], 0, 0, 0);
-        acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qhi[1][kc], acc[b][1], 0, 0, 0);
-        // keep this order in the schedule: the reads for block j + PF, then the MFMAs of block j
-        if (j + PF < NJ) __builtin_amdgcn_sched_group_barrier(0x100, THREE ? 2 : 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, THREE ? 6 : 2, 0);
-    }
-}
+    // row blocks whose fragments are in flight ahead of the MFMAs: a lone wave per SIMD needs this many
+    // LDS reads outstanding to keep the LDS pipe, and with it the matrix pipe, busy
+    static constexpr int PF = cmin(CORR_LDS_PF, cmax(1, G::NB / G::NG));
+    static_assert(RG::NS >= 3, "the pipelined loop refills a slot one step after it waits for the next unit");
+    struct Frags { bf16x8 h[PF], l[PF]; };
+    using Voff = const int (&)[G::NG][G::ITERS];
+    using Acc = f32x4 (&)[G::NB][TWO ? 2 : 1];
+    using QF = const bf16x8 (&)[2][NCMAX];
 
-// The chunk loop of one level over NCMAX chunks starting at kc0.  Units 0 .. pre-1 were issued
-// by the caller (before the previous level's epilogue); the rest of the ring is filled here.
-template <int LVL, bool THREE, int U>
-struct KSteps {
-    using G = Geo<LVL, THREE>;
-    using RG = Ring<LVL, THREE>;
-    __device__ static __forceinline__ void fill(const BlockArgs& a, const ItemCtx& c,
-                                                const int (&voff)[G::NG][G::ITERS], int kc0, int pre) {
+    static constexpr int nj(int u) { return (G::NB - u % G::NG + G::NG - 1) / G::NG; }   // row blocks of unit u
+    // loads that may still be in flight behind unit u + 1 when step u waits for it
+    static constexpr int younger(int u) { return cmin(G::NU - 1, RG::NS - 1 + cmax(u - 1, 0)) - (u + 1); }
+
+    template <int U>
+    __device__ static __forceinline__ void fill(const BlockArgs& a, const ItemCtx& c, Voff voff, int kc0, int pre) {
         if constexpr (U < RG::NS) {
             if (U >= pre) issue_unit<LVL, THREE, U>(a, c, voff, kc0);
-            KSteps<LVL, THREE, U + 1>::fill(a, c, voff, kc0, pre);
+            fill<U + 1>(a, c, voff, kc0, pre);
         }
     }
-    __device__ static __forceinline__ void run(const BlockArgs& a, const ItemCtx& c, const unsigned char* smem,
-                                               const int (&voff)[G::NG][G::ITERS], int kc0,
-                                               const bf16x8 (&qhi)[2][NCMAX], const bf16x8 (&qlo)[2][NCMAX],
-                                               f32x4 (&acc)[G::NB][2], int frag_hi, int frag_lo, bool active) {
+    // fragment of row block j of unit U: lane holds channels 8*(lane/16)..+7 of row 16*j + lane%16
+    template <int U>
+    __device__ static __forceinline__ void read_frag(const unsigned char* smem, int j, int frag_hi, int frag_lo,
+                                                     bf16x8& h, bf16x8& l) {
+        const unsigned char* rows = smem + RG::slot_off(U % RG::NS) + j * 16 * G::ROWB;
+        h = *reinterpret_cast<const bf16x8*>(rows + frag_hi);
+        if (THREE) l = *reinterpret_cast<const bf16x8*>(rows + frag_lo);
+    }
+
+    template <int U>
+    __device__ static __forceinline__ void step(const BlockArgs& a, const ItemCtx& c, const unsigned char* smem,
+                                                Voff voff, int kc0, QF qhi, QF qlo, Acc acc,
+                                                int frag_hi, int frag_lo, Frags& f) {
         if constexpr (U < G::NU) {
-            wait_vm<G::ITERS * RG::younger(U)>();
-            __syncthreads();                     // unit U is in LDS for everyone; everyone is done with unit U - 1
-            if constexpr (U >= 1 && U - 1 + RG::NS < G::NU) issue_unit<LVL, THREE, U - 1 + RG::NS>(a, c, voff, kc0);
-            if (active && kc0 + U / G::NG < a.NC)
-                mfma_unit<LVL, THREE, U>(c, smem, qhi, qlo, acc, frag_hi, frag_lo);
-            KSteps<LVL, THREE, U + 1>::run(a, c, smem, voff, kc0, qhi, qlo, acc, frag_hi, frag_lo, active);
+            constexpr int g = U % G::NG, kc = U / G::NG;
+            constexpr int NJ = nj(U);
+            constexpr int JS = cmax(0, cmin(NJ / 2, NJ - PF));           // row block before which the step synchronises
+            constexpr bool HAS_NEXT = U + 1 < G::NU;
+            constexpr int IU = (U >= 1 && U - 1 + RG::NS < G::NU) ? U - 1 + RG::NS : -1;
+            static_assert(NJ >= PF, "a unit holds at least PF row blocks");
+            Frags nf;
+            {
+                bf16x8 wh[NJ + PF], wl[NJ + PF];
+#pragma unroll
+                for (int j = 0; j < PF; ++j) { wh[j] = f.h[j]; wl[j] = f.l[j]; }
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const int b = j * G::NG + g;
+                    if (j == JS && HAS_NEXT) {
+                        wait_vm<G::ITERS * (HAS_NEXT ? younger(U) : 0)>();
+                        __syncthreads();         // unit U + 1 is in LDS for everyone; everyone is done with unit U - 1
+                    }
+                    if (j + PF < NJ) read_frag<U>(smem, j + PF, frag_hi, frag_lo, wh[j + PF], wl[j + PF]);
+                    else if (HAS_NEXT) read_frag<(HAS_NEXT ? U + 1 : U)>(smem, j + PF - NJ, frag_hi, frag_lo, wh[j + PF], wl[j + PF]);
+                    if (THREE) {
+                        acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[j], qhi[0][kc], acc[b][0], 0, 0, 0);
+                        if (TWO) acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[j], qhi[1][kc], acc[b][1], 0, 0, 0);
+                        acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qlo[0][kc], acc[b][0], 0, 0, 0);
+                        if (TWO) acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qlo[1][kc], acc[b][1], 0, 0, 0);
+                    }
+                    acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qhi[0][kc], acc[b][0], 0, 0, 0);
+                    if (TWO) acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[j], qhi[1][kc], acc[b][1], 0, 0, 0);
+                    // nothing moves across this point: the reads for block j + PF stay PF blocks ahead of their use
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (IU >= 0)
+                        if (j >= JS)
+                            issue_unit<LVL, THREE, (IU >= 0 ? IU : 0)>(a, c, voff, kc0, (j - JS) * G::ITERS / (NJ - JS),
+                                                                       (j - JS + 1) * G::ITERS / (NJ - JS));
+                }
+#pragma unroll
+                for (int j = 0; j < PF; ++j) { nf.h[j] = wh[NJ + j]; nf.l[j] = wl[NJ + j]; }
+            }
+            step<U + 1>(a, c, smem, voff, kc0, qhi, qlo, acc, frag_hi, frag_lo, nf);
         }
+    }
+
+    __device__ static __forceinline__ void run(const BlockArgs& a, const ItemCtx& c, const unsigned char* smem,
+                                               Voff voff, int kc0, int pre, QF qhi, QF qlo, Acc acc,
+                                               int frag_hi, int frag_lo) {
+        fill<0>(a, c, voff, kc0, pre);
+        wait_vm<G::ITERS * (RG::NS - 1)>();
+        __syncthreads();                                                 // unit 0 is in LDS for everyone
+        Frags f;
+#pragma unroll
+        for (int j = 0; j < PF; ++j) read_frag<0>(smem, j, frag_hi, frag_lo, f.h[j], f.l[j]);
+        step<0>(a, c, smem, voff, kc0, qhi, qlo, acc, frag_hi, frag_lo, f);
+        __syncthreads();                                                 // every wave is done with the ring
     }
 };
 
@@ -325,7 +357,7 @@ __device__ __forceinline__ void write_taps(const BlockArgs& a, const ItemCtx& c,
     float* o_lvl = a.out + (size_t)c.b * a.L * KK * a.HW + (size_t)(LVL * KK) * tap_stride;
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
-    const int q = (c.lane >> 4) * QW + h * 16 + (c.lane & 15), wave = c.wave;   // S column lane -> query slot
+    const int q = h * 64 + c.lane, wave = c.wave;           // S column = lane
     if (q < c.n) {
         const float inv = __uint_as_float((uint32_t)(127 - LVL) << 23);   // 2^-LVL
         const float cxl = c.q_cx[q] * inv, cyl = c.q_cy[q] * inv;
@@ -335,19 +367,22 @@ __device__ __forceinline__ void write_taps(const BlockArgs& a, const ItemCtx& c,
         // K = 9: columns 0..3, 3..5, 5..7, 7..9; otherwise an even split
         const int i0 = K == 9 ? (wave == 0 ? 0 : 2 * wave + 1) : wave * K / NW;
         const int i1 = K == 9 ? 2 * wave + 3 : (wave + 1) * K / NW;
-        const float* s = S + (ry * G::WSX + rx + i0) * 64 + c.lane;
+        const float* s = S + (ry * G::WSX + rx + i0) * SST + c.lane;
         float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride + (size_t)(i0 * K) * tap_stride;
         float left[K + 1], right[K + 1];
 #pragma unroll
-        for (int j = 0; j <= K; ++j) left[j] = s[j * G::WSX * 64];
+        for (int j = 0; j <= K; ++j) left[j] = s[j * G::WSX * SST];
         for (int i = i0; i < i1; ++i) {
-            s += 64;
+            s += SST;
 #pragma unroll
-            for (int j = 0; j <= K; ++j) right[j] = s[j * G::WSX * 64];
+            for (int j = 0; j <= K; ++j) right[j] = s[j * G::WSX * SST];
             float hprev = left[0] + fx * (right[0] - left[0]);
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 const float hcur = left[j + 1] + fx * (right[j + 1] - left[j + 1]);
+#ifdef CORR_DEBUG_NOSTORE
+                if (a.scale == 12345.f)
+#endif
                 o[(size_t)j * tap_stride] = (hprev + fy * (hcur - hprev)) * a.scale;    // 1/sqrt(D), once per tap
                 hprev = hcur;
             }
@@ -378,30 +413,30 @@ struct Plan {
     int pre;            // units already issued
 };
 
-// issue units 0 .. PRE-1 of level LVL (the slots above the running epilogue's S)
-template <int LVL, bool THREE, int U = 0>
-__device__ __forceinline__ void prefetch_units(const BlockArgs& a, const ItemCtx& c, Plan<LVL, THREE>& pl) {
-    using RG = Ring<LVL, THREE>;
-    if constexpr (U < RG::PRE) {
+// issue units U .. U1-1 of level LVL
+template <int LVL, bool THREE, int U, int U1>
+__device__ __forceinline__ void issue_units(const BlockArgs& a, const ItemCtx& c, Plan<LVL, THREE>& pl) {
+    if constexpr (U < U1) {
         issue_unit<LVL, THREE, U>(a, c, pl.voff, 0);
-        prefetch_units<LVL, THREE, U + 1>(a, c, pl);
+        issue_units<LVL, THREE, U + 1, U1>(a, c, pl);
     }
 }
 
+// Plan level LVL and issue its units 0 .. PRE-1 (the slots above the running epilogue's S).
 template <int LVL, bool THREE>
 __device__ __forceinline__ void begin_level(const BlockArgs& a, const ItemCtx& c, Plan<LVL, THREE>& pl) {
     pl.pre = 0;
     pl.touches = LVL < a.L && window_touches<LVL, THREE>(a, c);
     if (pl.touches) {
         plan<LVL, THREE>(a, c, pl.voff);
-        prefetch_units<LVL, THREE>(a, c, pl);
+        issue_units<LVL, THREE, 0, Ring<LVL, THREE>::PRE>(a, c, pl);
         pl.pre = Ring<LVL, THREE>::PRE;
     }
 }
 
 // One level of one work item.  On entry `pl` holds the staging plan and units 0 .. pl.pre-1 are
 // in flight; before its own epilogue the level plans the next one and issues its first units.
-template <int LVL, bool THREE, bool BIGD, bool NHWC, class NextPlan>
+template <int LVL, bool THREE, bool BIGD, bool NHWC, bool TWO, class NextPlan>
 __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
                                            bf16x8 (&qhi)[2][NCMAX], bf16x8 (&qlo)[2][NCMAX],
                                            Plan<LVL, THREE>& pl, NextPlan& nx) {
@@ -417,11 +452,13 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
         return;
     }
 
-    f32x4 acc[G::NB][2];
+    constexpr int NH = TWO ? 2 : 1;                          // column blocks per wave
+    f32x4 acc[G::NB][NH];
 #pragma unroll
-    for (int i = 0; i < G::NB; ++i) { acc[i][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[i][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int i = 0; i < G::NB; ++i)
+#pragma unroll
+        for (int h = 0; h < NH; ++h) acc[i][h] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const bool active = wave * QW < c.n;                     // this wave has queries
     // fragment read: lane holds channels 8*(lane/16)..+7 of row 16*j + lane%16 of a slot
     const int fr = lane & 15, fk = lane >> 4;
     const int frag_hi = fr * G::ROWB + ((fk ^ G::swz(fr)) << 4);
@@ -429,31 +466,51 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
 
     for (int kc0 = 0; kc0 < (BIGD ? a.NC : 1); kc0 += NCMAX) {
         if (BIGD && (kc0 > 0 || LVL > 0)) load_queries<THREE>(a, c, kc0, qhi, qlo);
-        KSteps<LVL, THREE, 0>::fill(a, c, pl.voff, kc0, kc0 == 0 ? pl.pre : 0);
-        KSteps<LVL, THREE, 0>::run(a, c, smem, pl.voff, kc0, qhi, qlo, acc, frag_hi, frag_lo, active);
-        __syncthreads();                                     // every wave is done with the ring
+        KLoop<LVL, THREE, TWO>::run(a, c, smem, pl.voff, kc0, kc0 == 0 ? pl.pre : 0, qhi, qlo, acc, frag_hi, frag_lo);
     }
     TRACE(2 + 2 * LVL);
     begin_next();                                            // loads into the slots above S fly under the tap writes
+    if (LVL == 0) TRACE(10);
 
-    // lane holds queries 32*wave + 16*h + lane % 16, points 4*(lane/16)+v of every row block.
-    // Round h of the epilogue takes column block h of every wave: S column 16*wave + lane%16.
+    // lane holds queries 64*h + 16*wave + lane % 16, points 4*(lane/16)+v of every row block.
+    // Round h of the epilogue takes column block h of every wave: S column 16*wave + lane%16 = query 64*h + column.
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        if (h * 16 < c.n) {                                  // uniform
-            if (active) {
+    for (int h = 0; h < NH; ++h) {
+        {
+            {
+                // straight from the accumulator registers (inline assembly: left to itself the compiler
+                // copies every accumulator into ordinary registers first and spills the query fragments)
+                unsigned addr = c.lds_base + ((4 * (lane >> 4)) * SST + wave * 16 + (lane & 15)) * 4;
 #pragma unroll
-                for (int b = 0; b < G::NB; ++b)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        S[(b * 16 + 4 * (lane >> 4) + v) * 64 + wave * 16 + (lane & 15)] = acc[b][h][v];
+                for (int b = 0; b < G::NB; ++b) {
+                    asm volatile("ds_write_b32 %0, %1\n\tds_write_b32 %0, %2 offset:%5\n\t"
+                                 "ds_write_b32 %0, %3 offset:%6\n\tds_write_b32 %0, %4 offset:%7"
+                                 :: "v"(addr), "a"(acc[b][h][0]), "a"(acc[b][h][1]), "a"(acc[b][h][2]), "a"(acc[b][h][3]),
+                                    "n"(SST * 4), "n"(2 * SST * 4), "n"(3 * SST * 4) : "memory");
+                    addr += 16 * SST * 4;
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
             __syncthreads();
+            if (LVL == 0) TRACE(11 + 2 * h);
             write_taps<LVL, THREE, NHWC>(a, c, S, h);
+            if (LVL == 0) TRACE(12 + 2 * h);
             __syncthreads();                                 // S is dead
         }
     }
     TRACE(3 + 2 * LVL);
+}
+
+template <bool THREE, bool BIGD, bool NHWC, bool TWO>
+__device__ __forceinline__ void run_levels(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
+                                           bf16x8 (&qhi)[2][NCMAX], bf16x8 (&qlo)[2][NCMAX], Plan<0, THREE>& p0) {
+    Plan<1, THREE> p1;
+    Plan<2, THREE> p2;
+    Plan<3, THREE> p3;
+    level_pass<0, THREE, BIGD, NHWC, TWO>(a, c, smem, qhi, qlo, p0, p1);
+    if (a.L > 1) level_pass<1, THREE, BIGD, NHWC, TWO>(a, c, smem, qhi, qlo, p1, p2);
+    if (a.L > 2) level_pass<2, THREE, BIGD, NHWC, TWO>(a, c, smem, qhi, qlo, p2, p3);
+    if (a.L > 3) level_pass<3, THREE, BIGD, NHWC, TWO>(a, c, smem, qhi, qlo, p3, p3);
 }
 
 template <bool THREE, bool BIGD, bool NHWC>
@@ -474,16 +531,16 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     const int4 item = a.items[k];
     ItemCtx c;
     c.item = k;
-    c.tid = threadIdx.x; c.lane = c.tid & 63; c.wave = c.tid >> 6;
+    c.tid = threadIdx.x; c.lane = c.tid & 63;
+    // the wave index as a scalar: branches on it must be scalar branches, or the compiler copies every
+    // accumulator around each of them
+    c.wave = __builtin_amdgcn_readfirstlane(c.tid >> 6);
     c.n = item.z;
     corr_cell_coords(a.g, item.x, &c.b, &c.u, &c.v);
     c.u += a.g.u_min; c.v += a.g.v_min;
     c.q_pix = q_pix; c.q_cx = q_cx; c.q_cy = q_cy;
-    c.lds_wave = __builtin_amdgcn_readfirstlane(
-        (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + c.wave * 1024);
-#ifdef CORR_DEBUG_SYNC_STAGE
-    c.dbg_smem = smem;
-#endif
+    c.lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    c.lds_wave = __builtin_amdgcn_readfirstlane(c.lds_base + c.wave * 1024);
     const uint64_t base = reinterpret_cast<uint64_t>(a.f2s);
     c.rsrc[0] = (int)(uint32_t)base; c.rsrc[1] = (int)((base >> 32) & 0xffffu);
     // the range check covers voffset + soffset, so the resource spans all chunk planes
@@ -491,33 +548,31 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     c.rsrc_null = c.rsrc; c.rsrc_null[2] = 0;
 
     TRACE(0);
-    // level 0's first units start to move before anything else
+    // level 0's first unit starts to move before anything else
     Plan<0, THREE> p0;
-    begin_level<0, THREE>(a, c, p0);
+    p0.pre = 0;
+    p0.touches = window_touches<0, THREE>(a, c);
+    if (p0.touches) { plan<0, THREE>(a, c, p0.voff); issue_units<0, THREE, 0, 1>(a, c, p0); }
 
     if (c.tid < CORR_GROUP) {
         int pix = -1;
-        float cx = 0.f, cy = 0.f;
+        float2 xy = make_float2(0.f, 0.f);
         if (c.tid < c.n) {
             pix = a.perm[item.y + c.tid] - c.b * a.HW;
-            cx = a.coords[((size_t)c.b * 2 + 0) * a.HW + pix];
-            cy = a.coords[((size_t)c.b * 2 + 1) * a.HW + pix];
+            xy = a.sorted_c[item.y + c.tid];
         }
-        q_pix[c.tid] = pix; q_cx[c.tid] = cx; q_cy[c.tid] = cy;
+        q_pix[c.tid] = pix; q_cx[c.tid] = xy.x; q_cy[c.tid] = xy.y;
     }
     __syncthreads();
 
     bf16x8 qhi[2][NCMAX], qlo[2][NCMAX];
-    load_queries<THREE>(a, c, 0, qhi, qlo);
+    load_queries<THREE>(a, c, 0, qhi, qlo);        // ends with a full wait: unit 0 is in as well
+    if (p0.touches) { issue_units<0, THREE, 1, Ring<0, THREE>::PRE>(a, c, p0); p0.pre = Ring<0, THREE>::PRE; }
     TRACE(1);
 
-    Plan<1, THREE> p1;
-    Plan<2, THREE> p2;
-    Plan<3, THREE> p3;
-    level_pass<0, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, p0, p1);
-    if (a.L > 1) level_pass<1, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, p1, p2);
-    if (a.L > 2) level_pass<2, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, p2, p3);
-    if (a.L > 3) level_pass<3, THREE, BIGD, NHWC>(a, c, smem, qhi, qlo, p3, p3);
+    // items of up to 64 queries fill one column block per wave: half the MFMAs and one epilogue round
+    if (c.n > 64) run_levels<THREE, BIGD, NHWC, true>(a, c, smem, qhi, qlo, p0);
+    else run_levels<THREE, BIGD, NHWC, false>(a, c, smem, qhi, qlo, p0);
 }
 
 template <bool THREE, bool BIGD, bool NHWC>
@@ -528,7 +583,7 @@ hipError_t launch_items(const corr_pyramid* p, const BinWs& ws, const LookupArgs
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (attr != hipSuccess) return attr;
     BlockArgs a;
-    a.f1s = p->f1_split; a.f2s = p->f2_split; a.coords = q.coords; a.perm = ws.perm; a.items = ws.items;
+    a.f1s = p->f1_split; a.f2s = p->f2_split; a.perm = ws.perm; a.sorted_c = ws.sorted_c; a.items = ws.items;
     a.n_items = ws.n_items; a.out = q.out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L;
     a.tap_stride = corr_tap_stride(p, q); a.pix_stride = corr_pix_stride(p, q);
     a.g = p->grid;

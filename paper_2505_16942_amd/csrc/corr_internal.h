@@ -13,7 +13,7 @@
 #define CORR_R 4               // largest lookup radius; the cell grid is laid out for it
 #define CORR_LOG_CX 4          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
 #define CORR_LOG_CY 3
-#define CORR_SUB (1 << CORR_LOG_CY)   // sub-bins per cell: one per target row, so a cell's queries come sorted by row
+#define CORR_SUB 8             // sub-bins per cell: source row mod 8, so a cell's queries come as runs of source pixels, row by row
 #define CORR_LOG_TX 2          // super-tile: 2^LOG_TX x 2^LOG_TY cells whose ids are consecutive
 #define CORR_LOG_TY 3
 #define CORR_TILE_CELLS (1 << (CORR_LOG_TX + CORR_LOG_TY))
@@ -47,18 +47,19 @@ __host__ __device__ static inline void corr_cell_coords(const CellGrid& g, int i
 
 // Per-lookup planning workspace (device memory).  Sized by corr_ws_layout().
 struct BinWs {
-    int* bin_count;                // [nbins] zero between calls; bin = cell * CORR_SUB + (target row & (CORR_SUB - 1))
+    int* bin_count;                // [nbins] zero between calls; bin = cell * CORR_SUB + (source row & (CORR_SUB - 1))
     int* bin_off;                  // [nbins] exclusive prefix of counts
     int* q_bin;                    // [B*H*W] bin id or -1
     int* q_rank;                   // [B*H*W] slot within the bin
     int* perm;                     // [B*H*W] queries sorted by bin
+    float2* sorted_c;              // [B*H*W] their coordinates (x, y), in the same order
     int4* items;                   // [max_items] {cell id, first perm index, n queries, 0}
     int* n_items;                  // [4]: items, binned queries, count-kernel tickets, 0
     long long* stats;              // [CORR_NSTATS]: 8+4*l+{0,1,2,3} per level
     int ncells, nbins, max_items;
 };
 // Byte offsets of the workspace arrays inside one allocation of `total` bytes.
-struct WsLayout { size_t bin_count, bin_off, q_bin, q_rank, perm, items, n_items, stats, total; };
+struct WsLayout { size_t bin_count, bin_off, q_bin, q_rank, perm, sorted_c, items, n_items, stats, total; };
 
 struct corr_pyramid {
     int B, H, W, D, L;
@@ -113,6 +114,7 @@ static inline WsLayout corr_ws_layout(int BN, int ncells) {
     w.q_bin = o; o = up(o + (size_t)BN * 4);
     w.q_rank = o; o = up(o + (size_t)BN * 4);
     w.perm = o; o = up(o + (size_t)BN * 4);
+    w.sorted_c = o; o = up(o + (size_t)BN * 8);
     w.items = o; o = up(o + (size_t)corr_max_items(BN, ncells) * 16);
     w.n_items = o; o = up(o + 16);
     w.stats = o; o = up(o + CORR_NSTATS * 8);
@@ -125,7 +127,8 @@ static inline BinWs corr_ws_carve(void* mem, int BN, int ncells) {
     BinWs s;
     s.bin_count = reinterpret_cast<int*>(m + w.bin_count); s.bin_off = reinterpret_cast<int*>(m + w.bin_off);
     s.q_bin = reinterpret_cast<int*>(m + w.q_bin); s.q_rank = reinterpret_cast<int*>(m + w.q_rank);
-    s.perm = reinterpret_cast<int*>(m + w.perm); s.items = reinterpret_cast<int4*>(m + w.items);
+    s.perm = reinterpret_cast<int*>(m + w.perm); s.sorted_c = reinterpret_cast<float2*>(m + w.sorted_c);
+    s.items = reinterpret_cast<int4*>(m + w.items);
     s.n_items = reinterpret_cast<int*>(m + w.n_items); s.stats = reinterpret_cast<long long*>(m + w.stats);
     s.ncells = ncells; s.nbins = ncells * CORR_SUB; s.max_items = corr_max_items(BN, ncells);
     return s;
