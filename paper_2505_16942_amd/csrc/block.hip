@@ -138,7 +138,7 @@ struct ItemCtx {
     const float* q_cy;
     unsigned lds_base;       // LDS byte address of smem
     unsigned lds_wave;       // LDS byte address of smem + wave * 1024 (uniform)
-    i32x4 rsrc, rsrc_null;   // buffer resources: all chunk planes of f2s; an empty buffer
+    i32x4 rsrc;              // buffer resource: all chunk planes of f2s
 };
 
 // 16 bytes per lane from a buffer straight into LDS at lds_base + lane * 16.  A lane whose
@@ -201,8 +201,10 @@ __device__ __forceinline__ void issue_unit(const BlockArgs& a, const ItemCtx& c,
     constexpr int g = U % G::NG, slot = U % RG::NS;
     const int kc = kc0 + U / G::NG;
     const bool real = kc < a.NC;                                  // uniform
-    const i32x4 rs = real ? c.rsrc : c.rsrc_null;
-    const unsigned soff = real ? (unsigned)kc * a.f2_plane_bytes : 0u;
+    // a chunk past the last one reads an empty buffer (zeros); readfirstlane keeps the operands scalar
+    i32x4 rs = c.rsrc;
+    rs[2] = __builtin_amdgcn_readfirstlane(real ? c.rsrc[2] : 0);
+    const unsigned soff = __builtin_amdgcn_readfirstlane(real ? (unsigned)kc * a.f2_plane_bytes : 0u);
 #pragma unroll
     for (int it = 0; it < G::ITERS; ++it)
         if (it >= it0 && it < it1)                                // constants once the callers' loops are unrolled
@@ -542,10 +544,10 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     c.lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     c.lds_wave = __builtin_amdgcn_readfirstlane(c.lds_base + c.wave * 1024);
     const uint64_t base = reinterpret_cast<uint64_t>(a.f2s);
-    c.rsrc[0] = (int)(uint32_t)base; c.rsrc[1] = (int)((base >> 32) & 0xffffu);
+    c.rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)base);
+    c.rsrc[1] = __builtin_amdgcn_readfirstlane((int)((base >> 32) & 0xffffu));
     // the range check covers voffset + soffset, so the resource spans all chunk planes
-    c.rsrc[2] = (int)(a.f2_plane_bytes * (unsigned)a.NC); c.rsrc[3] = 0x00020000;
-    c.rsrc_null = c.rsrc; c.rsrc_null[2] = 0;
+    c.rsrc[2] = __builtin_amdgcn_readfirstlane((int)(a.f2_plane_bytes * (unsigned)a.NC)); c.rsrc[3] = 0x00020000;
 
     TRACE(0);
     // level 0's first unit starts to move before anything else
