@@ -22,6 +22,18 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
+def kernel_source_sha() -> str:
+    """sha256 over the library's kernel sources, in name order: ties a counter summary to the code it measured."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2505_16942_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,9 +52,13 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB (3 launches) so that a counter run "
                          "sees a kernel of known HBM traffic")
+    ap.add_argument("--print-source-sha", action="store_true", help="print the kernel-source hash and exit")
     ap.add_argument("--compare-modes", action="store_true",
                     help="additionally time the on-demand and full-volume reference modes (one lookup each)")
     args = ap.parse_args()
+    if args.print_source_sha:
+        print(kernel_source_sha())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
@@ -107,15 +123,27 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    cb.corr_profile_enable(True)
+    # the headline: K steps between synchronisations, the library's profiling hook off
+    cb.corr_profile_enable(False)
     torch.cuda.synchronize()
     tb = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     te = time.perf_counter()
+
+    # per-kernel durations: a separate pass over the same steps with HIP events around each kernel on the
+    # launch stream (the library records them); the hook keeps PROF_CAP lookups, so the pass is sized to fit
+    PROF_CAP = 256
+    prof_steps = max(1, min(args.steps, PROF_CAP // nl))
+    cb.corr_profile_enable(True)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
     prof = cb.corr_profile_read()
     cb.corr_profile_enable(False)
+    if prof.get("dropped", 0):
+        print("bench.py: warning: %d profiled lookups were dropped (cap %d)" % (prof["dropped"], PROF_CAP), file=sys.stderr)
 
     ms_per_step = (te - tb) * 1e3 / args.steps
     lookups_per_call = B * N * L * K * K
@@ -142,32 +170,57 @@ def main() -> int:
     bin_ms = prof["binning_ms"] / nprof
     used_pq = float(np.mean([s["used_point_queries"] for s in stats]))
     mma_pq = float(np.mean([s["mma_point_queries"] for s in stats]))
-    flops = 2.0 * D * terms * used_pq            # algorithmic: window points x real queries x D x bf16 terms
-    achieved_tf = flops / (blk_ms * 1e-3) / 1e12
+    # flops the method defines: one D-long dot product per (window point, real query) pair; the bf16x3
+    # mode runs each as three bf16 MFMA terms, which is more machine work, not more useful work
+    flops_1 = 2.0 * D * used_pq
+    flops_run = flops_1 * terms
     npyr = sum((H >> l) * (W >> l) for l in range(L))
     # algorithmic HBM bytes of one launch: fmap1 and every pyramid pixel once (bf16 hi+lo = 4 B per
     # element; bf16 mode on hi-only records 2 B), coords, the sorted query list, `out` once
     feat_b = 4 if terms == 3 else 2
     bytes_alg = B * (N * D * feat_b + npyr * D * feat_b + N * 8 + N * 4 + N * L * K * K * 4)
+    hbm_floor_ms = bytes_alg / (PEAK_HBM_GBS * 1e9) * 1e3
+    mfma_floor_ms = flops_run / (PEAK_BF16_TFLOPS * 1e12) * 1e3
     hbm_gbs = bytes_alg / (blk_ms * 1e-3) / 1e9
-    roofline = {
-        "bound": "mfma", "achieved": round(achieved_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
+    tf_run = flops_run / (blk_ms * 1e-3) / 1e12
+    tf_1 = flops_1 / (blk_ms * 1e-3) / 1e12
+    if hbm_floor_ms >= mfma_floor_ms:       # the binding roofline is the one with the larger time floor
+        roofline = {"bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(hbm_gbs / PEAK_HBM_GBS, 4)}
+    else:
+        roofline = {"bound": "mfma", "achieved": round(tf_run, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf_run / PEAK_BF16_TFLOPS, 4)}
+    roofline.update({
+        "traffic": None, "traffic_source": None,
         "kernel": "block_kernel (contraction + bilinear epilogue, all %d levels)" % L,
-        "avg_launch_ms": round(blk_ms, 4),
-        "flops_per_launch": flops,
-        "flops_counted": "2*D*%d bf16 terms*window points*real queries, summed over levels" % terms,
-        "issued_over_counted": round(mma_pq / max(used_pq, 1.0), 4),
-        "hbm_algorithmic_bytes_per_launch": bytes_alg,
-        "hbm_achieved_GBs": round(hbm_gbs, 1), "hbm_frac": round(hbm_gbs / PEAK_HBM_GBS, 4),
-    }
+        "avg_launch_ms": round(blk_ms, 4), "launches_timed": int(prof["lookups"]),
+        "algorithmic_bytes_per_launch": bytes_alg,
+        "floors_ms": {"hbm": round(hbm_floor_ms, 4), "mfma_as_run": round(mfma_floor_ms, 4)},
+        "hbm": {"achieved_GBs": round(hbm_gbs, 1), "frac": round(hbm_gbs / PEAK_HBM_GBS, 4)},
+        "mfma": {"flops_method_1term": flops_1, "flops_as_run_%dterm" % terms: flops_run,
+                 "TFLOPs_1term": round(tf_1, 2), "frac_1term": round(tf_1 / PEAK_BF16_TFLOPS, 4),
+                 "TFLOPs_as_run": round(tf_run, 2), "frac_as_run": round(tf_run / PEAK_BF16_TFLOPS, 4),
+                 "issued_over_counted": round(mma_pq / max(used_pq, 1.0), 4),
+                 "counted": "2*D*window points*real queries summed over levels; as_run multiplies by the %d bf16 "
+                            "terms of this precision; issued adds padding rows and empty query slots" % terms},
+    })
 
-    # measured HBM traffic of the block kernel, if a counter summary for this workload is committed
+    # HBM traffic of the block kernel is not measured by this run (it needs hardware counters).  A committed
+    # counter summary is quoted only if it says it was taken on exactly the kernel sources in this tree.
     traffic_file = os.path.join(ROOT, "profiles", "block_kernel_%s_hbm_traffic.txt" % args.config)
     if terms == 3 and args.out_layout == "nchw" and os.path.exists(traffic_file):
+        fields = {}
         for line in open(traffic_file):
-            if line.startswith("traffic_bytes_per_launch:"):
-                roofline["traffic"] = float(line.split(":")[1])
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                fields[k.strip()] = v.strip()
+        if fields.get("kernel_source_sha256", "")[:16] == kernel_source_sha()[:16] and "traffic_bytes_per_launch" in fields:
+            roofline["traffic"] = float(fields["traffic_bytes_per_launch"])
+            roofline["traffic_source"] = {"file": os.path.relpath(traffic_file, ROOT), "measured": fields.get("date", "?"),
+                                          "kernel_source_sha256": fields["kernel_source_sha256"][:16],
+                                          "note": "rocprofv3 FETCH_SIZE/WRITE_SIZE runs of this command, not this run"}
+        else:
+            roofline["traffic_source"] = "committed counter summary is for other kernel sources; not quoted"
 
     peak_bytes = int(torch.cuda.max_memory_allocated()) + pyr.bytes()
     result = {

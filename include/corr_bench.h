@@ -76,6 +76,12 @@ corr_status corr_copy_f32(float* dst, const float* src, size_t n, void* stream);
  */
 corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32_t* items, size_t items_cap,
                                  int32_t* perm, size_t perm_cap, void* stream);
+/*
+ * Test hook (host only, no GPU work): the block kernel's launch grid for a workspace that can hold
+ * `max_items` work items, and which item each workgroup takes: map[w] for w < *grid.  Pass map = NULL
+ * to get the grid size alone; CORR_ERR_INVALID_ARG if map_cap < *grid.
+ */
+corr_status corr_debug_item_map(int max_items, int32_t* map, size_t map_cap, int* grid);
 /* Test hook: absolute cell coordinates (floor(x) >> 4, floor(y) >> 3) and batch item of a cell id. */
 corr_status corr_debug_cell_coords(const corr_pyramid* pyr, int cell_id, int* b, int* u, int* v);
 /*

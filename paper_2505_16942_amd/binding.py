@@ -32,7 +32,7 @@ EXPORTS = [
 # measurement and test hooks (include/corr_bench.h)
 BENCH_EXPORTS = [
     "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry", "corr_copy_f32",
-    "corr_debug_read_plan", "corr_debug_cell_coords", "corr_debug_read_level",
+    "corr_debug_read_plan", "corr_debug_cell_coords", "corr_debug_read_level", "corr_debug_item_map",
 ]
 
 
@@ -102,6 +102,8 @@ def load_library():
     lib.corr_debug_read_plan.restype = ci
     lib.corr_debug_cell_coords.argtypes = [vp, ci] + [ctypes.POINTER(ci)] * 3
     lib.corr_debug_cell_coords.restype = ci
+    lib.corr_debug_item_map.argtypes = [ci, ctypes.POINTER(ctypes.c_int32), ctypes.c_size_t, ctypes.POINTER(ci)]
+    lib.corr_debug_item_map.restype = ci
     lib.corr_debug_read_level.argtypes = [vp, cu, ci, ctypes.POINTER(ctypes.c_float), vp]
     lib.corr_debug_read_level.restype = ci
     lib.corr_status_string.argtypes = [ci]
@@ -283,6 +285,21 @@ def corr_debug_read_plan(pyramid: Pyramid):
     if st != CORR_OK:
         raise CorrError(st, "corr_debug_read_plan")
     return items[:counts[0]].copy(), perm[:counts[1]].copy()
+
+
+def corr_debug_item_map(max_items: int):
+    """(grid, map): the block kernel's grid for `max_items` and the item index each workgroup takes."""
+    import numpy as np
+    lib = load_library()
+    grid = ctypes.c_int()
+    st = lib.corr_debug_item_map(int(max_items), None, 0, ctypes.byref(grid))
+    if st != CORR_OK:
+        raise CorrError(st, "corr_debug_item_map")
+    m = np.zeros(grid.value, np.int32)
+    st = lib.corr_debug_item_map(int(max_items), m.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), m.size, ctypes.byref(grid))
+    if st != CORR_OK:
+        raise CorrError(st, "corr_debug_item_map")
+    return grid.value, m
 
 
 def corr_debug_cell_coords(pyramid: Pyramid, cell_id: int):

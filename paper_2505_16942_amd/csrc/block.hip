@@ -50,7 +50,6 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int R = CORR_BLOCK_R, K = 2 * R + 1, KK = K * K;
 constexpr int CX = 1 << CORR_LOG_CX, CY = 1 << CORR_LOG_CY;
 constexpr int NW = 4, NT = 64 * NW;
-constexpr int XCD_RUN = 32;                            // consecutive items dealt to one XCD; a power of two
 constexpr int NCMAX = CORR_BLOCK_MAX_D / CORR_CHUNK;   // chunks of query fragments a wave holds
 constexpr int LDS_BYTES = 160 * 1024;
 constexpr int META_BYTES = CORR_GROUP * 12;
@@ -522,13 +521,9 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP);
     float* q_cy = q_cx + CORR_GROUP;
 
-    // XCD-aware item choice: workgroup w runs on XCD w % 8.  Items are dealt to the XCDs in runs
-    // of XCD_RUN consecutive items (neighbouring cells share window rows and columns, so they
-    // should share an L2), round robin, so that cheap border regions do not all land on the same
-    // XCD.  The grid is a multiple of 8 * XCD_RUN, so every item index is produced exactly once.
+    // XCD-aware item choice; the grid covers the largest possible item count, the tail exits here
     const int n_items = *a.n_items;
-    const int j = blockIdx.x >> 3;
-    const int k = ((j / XCD_RUN) * 8 + (blockIdx.x & 7)) * XCD_RUN + j % XCD_RUN;
+    const int k = corr_item_of_workgroup(blockIdx.x);
     if (k >= n_items) return;
     const int4 item = a.items[k];
     ItemCtx c;
@@ -598,7 +593,7 @@ hipError_t launch_items(const corr_pyramid* p, const BinWs& ws, const LookupArgs
 #ifdef CORR_TRACE
     a.trace = g_corr_trace;
 #endif
-    const int grid = (ws.max_items + 8 * XCD_RUN - 1) / (8 * XCD_RUN) * (8 * XCD_RUN);
+    const int grid = corr_block_grid(ws.max_items);
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), LDS_BYTES, s, a);
     return hipGetLastError();
 }

@@ -460,6 +460,15 @@ corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32
     return hipStreamSynchronize(s) == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 
+corr_status corr_debug_item_map(int max_items, int32_t* map, size_t map_cap, int* grid) {
+    if (max_items < 0 || !grid) return CORR_ERR_INVALID_ARG;
+    *grid = corr_block_grid(max_items);
+    if (!map) return CORR_OK;
+    if (map_cap < (size_t)*grid) return CORR_ERR_INVALID_ARG;
+    for (int w = 0; w < *grid; ++w) map[w] = corr_item_of_workgroup(w);
+    return CORR_OK;
+}
+
 corr_status corr_debug_cell_coords(const corr_pyramid* pyr, int cell_id, int* b, int* u, int* v) {
     if (!pyr || !b || !u || !v || cell_id < 0 || cell_id >= corr_ncells(pyr->grid, pyr->B)) return CORR_ERR_INVALID_ARG;
     corr_cell_coords(pyr->grid, cell_id, b, u, v);

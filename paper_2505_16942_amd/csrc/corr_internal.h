@@ -45,6 +45,19 @@ __host__ __device__ static inline void corr_cell_coords(const CellGrid& g, int i
     *b = tile / (g.tnx * g.tny);
 }
 
+// Which work item workgroup w of the block kernel takes.  Workgroup w runs on XCD w % 8; items are dealt to
+// the XCDs in runs of CORR_XCD_RUN consecutive items (neighbouring cells share window rows and columns, so
+// they should share an L2), round robin, so that cheap border regions do not all land on one XCD.  On a grid
+// that is a multiple of 8 * CORR_XCD_RUN workgroups (corr_block_grid) this is a permutation of the grid.
+#define CORR_XCD_RUN 32
+__host__ __device__ static inline int corr_item_of_workgroup(int w) {
+    const int j = w >> 3;
+    return ((j / CORR_XCD_RUN) * 8 + (w & 7)) * CORR_XCD_RUN + j % CORR_XCD_RUN;
+}
+static inline int corr_block_grid(int max_items) {
+    return (max_items + 8 * CORR_XCD_RUN - 1) / (8 * CORR_XCD_RUN) * (8 * CORR_XCD_RUN);
+}
+
 // Per-lookup planning workspace (device memory).  Sized by corr_ws_layout().
 struct BinWs {
     int* bin_count;                // [nbins] zero between calls; bin = cell * CORR_SUB + (source row & (CORR_SUB - 1))

@@ -7,6 +7,8 @@
 
 namespace {
 
+constexpr size_t MAX_BLOCKS = 1u << 22;     // of 256 threads: 2^30 threads per launch, the kernels stride over the rest
+
 // C[p][q] = scale * sum_d A[p][d] * B[q][d]; 64x64 tile per workgroup, 4x4 per thread.
 __global__ __launch_bounds__(256) void vol_gemm_kernel(const float* __restrict__ A, const float* __restrict__ Bm,
                                                        float* __restrict__ C, int N, int D, float scale) {
@@ -45,13 +47,14 @@ __global__ __launch_bounds__(256) void vol_gemm_kernel(const float* __restrict__
 // dst[bp][v][u] = 0.25 * (src[bp][2v][2u] + src[bp][2v][2u+1] + src[bp][2v+1][2u] + src[bp][2v+1][2u+1])
 __global__ __launch_bounds__(256) void vol_pool_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                        size_t rows, int Hs, int Ws, int Hd, int Wd) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t per = (size_t)Hd * Wd;
-    if (i >= rows * per) return;
-    const size_t bp = i / per;
-    const int vu = (int)(i - bp * per), v = vu / Wd, u = vu - v * Wd;
-    const float* s = src + bp * (size_t)Hs * Ws + (size_t)(2 * v) * Ws + 2 * u;
-    dst[i] = 0.25f * (((s[0] + s[1]) + s[Ws]) + s[Ws + 1]);
+    // grid-stride: a launch holds fewer than 2^32 threads, a pooled volume can hold more elements than that
+    const size_t per = (size_t)Hd * Wd, total = rows * per, step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += step) {
+        const size_t bp = i / per;
+        const int vu = (int)(i - bp * per), v = vu / Wd, u = vu - v * Wd;
+        const float* s = src + bp * (size_t)Hs * Ws + (size_t)(2 * v) * Ws + 2 * u;
+        dst[i] = 0.25f * (((s[0] + s[1]) + s[Ws]) + s[Ws + 1]);
+    }
 }
 
 struct FvArgs {
@@ -69,9 +72,8 @@ __device__ __forceinline__ float vol_at(const float* v, int H, int W, int y, int
 
 __global__ __launch_bounds__(256) void vol_sample_kernel(FvArgs a) {
     const int K = 2 * a.r + 1, KK = K * K;
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t total = (size_t)a.B * a.L * KK * a.HW;
-    if (i >= total) return;
+    const size_t total = (size_t)a.B * a.L * KK * a.HW, step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += step) {
     const int pix = (int)(i % a.HW);
     size_t rest = i / a.HW;
     const int t = (int)(rest % KK); rest /= KK;
@@ -93,6 +95,7 @@ __global__ __launch_bounds__(256) void vol_sample_kernel(FvArgs a) {
           + (1.f - fx) * fy * vol_at(vp, H, W, y0 + 1, x0) + fx * fy * vol_at(vp, H, W, y0 + 1, x0 + 1);
     }
     a.out[(size_t)b * a.L * KK * a.HW + (size_t)(l * KK + t) * a.tap_stride + (size_t)pix * a.pix_stride] = v;
+    }
 }
 
 }  // namespace
@@ -107,7 +110,8 @@ hipError_t launch_fullvol_build(const corr_pyramid* p, hipStream_t s) {
     for (int l = 1; l < p->L; ++l) {
         const size_t rows = (size_t)p->B * N;
         const size_t total = rows * p->Hl[l] * p->Wl[l];
-        hipLaunchKernelGGL(vol_pool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+        const size_t blocks = (total + 255) / 256;
+        hipLaunchKernelGGL(vol_pool_kernel, dim3((unsigned)(blocks < MAX_BLOCKS ? blocks : MAX_BLOCKS)), dim3(256), 0, s,
                            p->vol[l - 1], p->vol[l], rows, p->Hl[l - 1], p->Wl[l - 1], p->Hl[l], p->Wl[l]);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -125,6 +129,7 @@ hipError_t launch_fullvol_sample(const corr_pyramid* p, const LookupArgs& q, hip
     a.tap_stride = corr_tap_stride(p, q); a.pix_stride = corr_pix_stride(p, q);
     const int K = 2 * q.r + 1;
     const size_t total = (size_t)p->B * p->L * K * K * a.HW;
-    hipLaunchKernelGGL(vol_sample_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
+    const size_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(vol_sample_kernel, dim3((unsigned)(blocks < MAX_BLOCKS ? blocks : MAX_BLOCKS)), dim3(256), 0, s, a);
     return hipGetLastError();
 }

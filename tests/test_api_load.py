@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -78,3 +79,23 @@ def test_bin_geometry_matches_the_rule():
             assert ny == ((((H >> m) + 4) * (1 << m) - 1) >> 3) - ((-5 * (1 << m)) >> 3) + 1
     with pytest.raises(binding.CorrError):
         binding.corr_bin_geometry(4, 4, 4, 0)
+
+
+def test_every_work_item_has_exactly_one_workgroup():
+    """The block kernel's workgroup -> item mapping, enumerated on the host for every workspace size in a
+    range and for the sizes of the benchmark configurations: a permutation of the launch grid, and the grid
+    covers the largest item count the workspace can hold (an unvisited item would leave stale output)."""
+    from paper_2505_16942_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.skip("library not built")
+    sizes = list(range(0, 1200)) + [2047, 2048, 2049, 8191, 8192, 9713, 65535, 65537, 300001]
+    for max_items in sizes:
+        grid, m = binding.corr_debug_item_map(max_items)
+        assert grid >= max_items and grid % 8 == 0
+        assert np.array_equal(np.sort(m), np.arange(grid)), max_items
+    # consecutive items stay on one XCD (workgroup w runs on XCD w % 8) in runs of 32
+    grid, m = binding.corr_debug_item_map(4096)
+    xcd_of_item = np.empty(grid, np.int64)
+    xcd_of_item[m] = np.arange(grid) % 8
+    assert np.all(xcd_of_item.reshape(-1, 32) == xcd_of_item.reshape(-1, 32)[:, :1])
+    assert np.array_equal(xcd_of_item.reshape(-1, 32)[:8, 0], np.arange(8))
