@@ -302,7 +302,12 @@ def main() -> int:
             "value": idx.size / work_s, "unit": "lookups/s", "cores": corr_oracle.threads(), "kind": "oracle",
             "sample": "%d random queries x all %d taps of lookup 0 (%d lookups), fp64 per-tap oracle; "
                       "%.1f s of tap work, its per-pair preprocessing (%.1f s) excluded"
-                      % (nq, L * K * K, idx.size, work_s, prep_s)}
+                      % (nq, L * K * K, idx.size, work_s, prep_s),
+            # like for like with `value` (one preprocessing per pair, then every lookup of the step),
+            # extrapolated from the sample's tap rate
+            "whole_step_value": lookups_per_call * nl / (prep_s + lookups_per_call * nl * work_s / idx.size),
+            "whole_step_note": "lookups of one step / (measured per-pair preprocessing + the step's lookups at the "
+                               "sampled tap rate)"}
         result["parity_on_sample"] = {"max_abs_err": float(np.abs(got - vals).max()), "max_abs_C": maxc,
                                       "bound": (1e-4 if terms == 3 else 2e-2) * maxc}
     pyr.destroy()

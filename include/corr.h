@@ -78,7 +78,9 @@ typedef enum {
  *                  (those return CORR_ERR_MISSING_REP).
  *   reps         : mask of CORR_REP_*; corr_pyramid_build uses CORR_REP_SPLIT.
  * Limits: 1 <= L <= 4 with H >> (L-1) >= 1 and W >> (L-1) >= 1; D a multiple of 32, D <= 1024;
- * B*H*W*81*L < 2^31.  The library owns the pyramid; free it with corr_pyramid_destroy.
+ * B*H*W*81*L < 2^31; with P = B * (pixels of all L levels): P*D < 2^30, P < 2^24, and B*H*W*D < 2^30
+ * (32-bit offsets inside the stored representations).  Anything beyond returns CORR_ERR_UNSUPPORTED.
+ * The library owns the pyramid; free it with corr_pyramid_destroy.
  */
 corr_status corr_pyramid_build(const float* fmap1, const float* fmap2,
                                int B, int H, int W, int D, int L,

@@ -54,7 +54,7 @@ constexpr int NCMAX = CORR_BLOCK_MAX_D / CORR_CHUNK;   // chunks of query fragme
 constexpr int LDS_BYTES = 160 * 1024;
 constexpr int META_BYTES = CORR_GROUP * 12;
 constexpr int LDS_DATA = LDS_BYTES - META_BYTES;       // ring slots and S
-constexpr int OOB = (int)0x80000000u;                  // a buffer offset beyond the whole pyramid (< 2 GiB): loads zeros
+constexpr int OOB = (int)0x80000000u;                  // a buffer offset beyond any chunk plane (each is below 2 GiB): loads zeros
 static_assert(CORR_GROUP == 128 && NW == 4, "a wave owns two 16-query column blocks");
 
 struct BlockArgs {
@@ -137,14 +137,14 @@ struct ItemCtx {
     const float* q_cy;
     unsigned lds_base;       // LDS byte address of smem
     unsigned lds_wave;       // LDS byte address of smem + wave * 1024 (uniform)
-    i32x4 rsrc;              // buffer resource: all chunk planes of f2s
+    i32x4 rsrc;              // buffer resource: chunk plane 0 of f2s (each load rebases it to its own plane)
 };
 
 // 16 bytes per lane from a buffer straight into LDS at lds_base + lane * 16.  A lane whose
-// voffset + soffset lies beyond the resource's size writes zeros (measured on gfx950).
-__device__ __forceinline__ void dma16(i32x4 rsrc, unsigned lds_base, int voff, unsigned soff) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+// voffset lies beyond the resource's size writes zeros (measured on gfx950).
+__device__ __forceinline__ void dma16(i32x4 rsrc, unsigned lds_base, int voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
@@ -200,14 +200,18 @@ __device__ __forceinline__ void issue_unit(const BlockArgs& a, const ItemCtx& c,
     constexpr int g = U % G::NG, slot = U % RG::NS;
     const int kc = kc0 + U / G::NG;
     const bool real = kc < a.NC;                                  // uniform
-    // a chunk past the last one reads an empty buffer (zeros); readfirstlane keeps the operands scalar
-    i32x4 rs = c.rsrc;
+    // The resource covers this chunk's plane alone (a plane is below 2 GiB, all planes together need not
+    // be); a chunk past the last one reads an empty buffer (zeros).  readfirstlane keeps the operands scalar.
+    const uint64_t pb = ((uint64_t)(uint32_t)c.rsrc[1] << 32 | (uint32_t)c.rsrc[0]) + (uint64_t)(real ? kc : 0) * a.f2_plane_bytes;
+    i32x4 rs;
+    rs[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)pb);
+    rs[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(pb >> 32));
     rs[2] = __builtin_amdgcn_readfirstlane(real ? c.rsrc[2] : 0);
-    const unsigned soff = __builtin_amdgcn_readfirstlane(real ? (unsigned)kc * a.f2_plane_bytes : 0u);
+    rs[3] = c.rsrc[3];
 #pragma unroll
     for (int it = 0; it < G::ITERS; ++it)
         if (it >= it0 && it < it1)                                // constants once the callers' loops are unrolled
-            dma16(rs, c.lds_wave + RG::slot_off(slot) + it * 4096, voff[g][it], soff);
+            dma16(rs, c.lds_wave + RG::slot_off(slot) + it * 4096, voff[g][it]);
 }
 
 // Query fragments of this wave for chunks kc0 .. kc0+NCMAX-1: lane holds channels 8*(lane/16) .. +7 of
@@ -541,8 +545,7 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     const uint64_t base = reinterpret_cast<uint64_t>(a.f2s);
     c.rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)base);
     c.rsrc[1] = __builtin_amdgcn_readfirstlane((int)((base >> 32) & 0xffffu));
-    // the range check covers voffset + soffset, so the resource spans all chunk planes
-    c.rsrc[2] = __builtin_amdgcn_readfirstlane((int)(a.f2_plane_bytes * (unsigned)a.NC)); c.rsrc[3] = 0x00020000;
+    c.rsrc[2] = __builtin_amdgcn_readfirstlane((int)a.f2_plane_bytes); c.rsrc[3] = 0x00020000;
 
     TRACE(0);
     // level 0's first unit starts to move before anything else

@@ -22,7 +22,8 @@ corr_status check_dims(int B, int H, int W, int D, int L) {
     long long px = 0;
     for (int l = 0; l < L; ++l) px += (long long)(H >> l) * (W >> l);
     if ((long long)B * px * D * 2 >= (1LL << 31)) return CORR_ERR_UNSUPPORTED;   // 32-bit element offsets
-    if ((long long)B * px * D * 4 >= (1LL << 31)) return CORR_ERR_UNSUPPORTED;   // byte offsets into the split pyramid
+    if ((long long)B * px * 128 >= (1LL << 31)) return CORR_ERR_UNSUPPORTED;     // byte offsets inside one chunk plane of the split pyramid
+    if ((long long)B * H * W * D * 4 >= (1LL << 32)) return CORR_ERR_UNSUPPORTED;  // unsigned byte offsets into the split fmap1
     return CORR_OK;
 }
 

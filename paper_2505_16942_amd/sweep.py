@@ -7,10 +7,20 @@ pair — preprocessing (pyramid build in the representation the mode reads) plus
 `iterations` lookups — and the table reports the time of that job and the bytes
 the mode holds on the device (inputs + library + output).  Inputs are synthetic:
 random feature vectors as in the paper, feature maps of width W and height
-round(W * 436 / 1024) (the 1/8-resolution aspect of the paper's frames), query
+7 W / 16 (the shapes of the paper's table: 512 x 224 and so on), query
 centroids = pixel grid + a smooth motion field of amplitude W / 10 + N(0, 0.5)
 jitter redrawn for every lookup.  The paper's centroids come from RAFT on
 Sintel; these stand in for them.
+
+The last column cross-checks what was timed: the largest difference between the block mode's
+output and the on-demand mode's (a plain fp32 evaluation of Eq. 1, one wave per query) for the last
+lookup, as a fraction of the parity bound 1e-4 * max|C|.  Parity with the CPU oracle at these shapes
+is a test of its own (tests/test_gpu_sweep_points.py).
+
+The full-volume column is this library's reference mode: an untuned fp32 vector-ALU GEMM (about 46
+TFLOP/s) and an unfused pooling pass.  A tuned dense volume would be several times faster, so the
+width at which block mode overtakes it in this table flatters block mode; the memory columns do not
+depend on that.
 
 Usage (GPU machine, repository root):  python -m paper_2505_16942_amd.sweep [--quick]
 Prints a markdown table.
@@ -26,7 +36,7 @@ def _case(width: int, D: int, seed: int):
     import numpy as np
     import torch
     from . import synth
-    H = max(int(round(width * 436.0 / 1024.0)), 8)
+    H = max(width * 7 // 16, 8)
     W = width
     dev = torch.device("cuda:0")
     g = torch.Generator(device=dev)
@@ -52,6 +62,7 @@ def _run_point(width: int, iters: int, D: int, L: int = 4, r: int = 4, reps_time
     out = torch.empty((1, L * 81, H, W), dtype=torch.float32, device=f1.device)
     caller = (f1.numel() + f2.numel() + out.numel() + 2 * H * W) * 4
     res = {}
+    last = {}
     modes = [("block", cb.CORR_MODE_BLOCK, cb.CORR_PREC_BF16X3, cb.CORR_REP_SPLIT),
              ("block_bf16", cb.CORR_MODE_BLOCK, cb.CORR_PREC_BF16, cb.CORR_REP_BF16),
              ("ondemand", cb.CORR_MODE_ONDEMAND, cb.CORR_PREC_BF16X3, cb.CORR_REP_F32),
@@ -79,12 +90,17 @@ def _run_point(width: int, iters: int, D: int, L: int = 4, r: int = 4, reps_time
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / reps_timed
             res[name] = (ms, pyr.bytes() + caller)
+            if name in ("block", "ondemand"):
+                last[name] = out.clone()
         except cb.CorrError as e:
             if e.status != cb.CORR_ERR_OOM:
                 raise
             res[name] = ("OOM", cb.corr_full_volume_bytes(1, H, W, L) + caller)
         pyr.destroy()
         torch.cuda.empty_cache()
+    if "block" in last and "ondemand" in last:
+        maxc = float(last["ondemand"].abs().max())
+        res["check"] = float((last["block"] - last["ondemand"]).abs().max()) / (1e-4 * max(maxc, 1e-30))
     return H, W, res
 
 
@@ -107,8 +123,8 @@ def main(argv=None) -> int:
         points += [("Iterations", n, (base_w, n, base_d)) for n in (1, 8, 16, 24, 32)]
         points += [("Feature dimensionality", d, (base_w, base_it, d)) for d in (64, 128, 256, 512, 1024)]
     print("| variable | value | map HxW | block bf16x3 ms | block bf16 ms | on-demand ms | full volume ms | "
-          "block MB | on-demand MB | full volume MB |")
-    print("|---|---|---|---|---|---|---|---|---|---|")
+          "block MB | on-demand MB | full volume MB | block vs on-demand, max diff / bound |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
     for var, val, (w, it, d) in points:
         H, W, res = _run_point(w, it, d)
 
@@ -119,9 +135,9 @@ def main(argv=None) -> int:
         def mb(k):
             return "%.0f" % (res[k][1] / 1e6)
 
-        print("| %s | %d | %dx%d | %s | %s | %s | %s | %s | %s | %s |" % (
+        print("| %s | %d | %dx%d | %s | %s | %s | %s | %s | %s | %s | %.3f |" % (
             var, val, H, W, ms("block"), ms("block_bf16"), ms("ondemand"), ms("fullvolume"),
-            mb("block"), mb("ondemand"), mb("fullvolume")), flush=True)
+            mb("block"), mb("ondemand"), mb("fullvolume"), res.get("check", float("nan"))), flush=True)
     return 0
 
 
