@@ -23,15 +23,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
 def kernel_source_sha() -> str:
-    """sha256 over the library's kernel sources, in name order: ties a counter summary to the code it measured."""
-    import hashlib
-    csrc = os.path.join(ROOT, "paper_2505_16942_amd", "csrc")
-    h = hashlib.sha256()
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".h")):
-            h.update(name.encode())
-            h.update(open(os.path.join(csrc, name), "rb").read())
-    return h.hexdigest()
+    """sha256 over the library's kernel sources: ties a counter summary to the code it measured."""
+    from paper_2505_16942_amd.profile_summary import kernel_source_sha as sha
+    return sha()
 
 
 def main() -> int:

@@ -360,6 +360,9 @@ __device__ __forceinline__ void write_taps(const BlockArgs& a, const ItemCtx& c,
     // query's consecutive taps into wide stores
     const size_t tap_stride = NHWC ? 1 : (size_t)a.tap_stride;
     float* o_lvl = a.out + (size_t)c.b * a.L * KK * a.HW + (size_t)(LVL * KK) * tap_stride;
+    // NCHW: taps leave through a buffer resource over this level's KK planes of this batch item (below
+    // 2 GiB): the lane's pixel is the vector offset, the tap's plane a scalar offset, no address arithmetic
+    __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(o_lvl, 0, 0x7fffffff, 0x00020000);
     int xs, ys;
     window_origin<LVL>(c, xs, ys);
     const int q = h * 64 + c.lane, wave = c.wave;           // S column = lane
@@ -368,32 +371,41 @@ __device__ __forceinline__ void write_taps(const BlockArgs& a, const ItemCtx& c,
         const float cxl = c.q_cx[q] * inv, cyl = c.q_cy[q] * inv;
         const float flx = floorf(cxl), fly = floorf(cyl);
         const float fx = cxl - flx, fy = cyl - fly;
+        // horizontal weights carry the 1/sqrt(D) scale: tap = lerp_y(lerp_x) costs four operations
+        const float wr = fx * a.scale, wl = a.scale - wr;
         const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;         // in [0, CXL) x [0, CYL)
         // K = 9: columns 0..3, 3..5, 5..7, 7..9; otherwise an even split
         const int i0 = K == 9 ? (wave == 0 ? 0 : 2 * wave + 1) : wave * K / NW;
         const int i1 = K == 9 ? 2 * wave + 3 : (wave + 1) * K / NW;
         const float* s = S + (ry * G::WSX + rx + i0) * SST + c.lane;
-        float* o = o_lvl + (size_t)c.q_pix[q] * a.pix_stride + (size_t)(i0 * K) * tap_stride;
+        const int pix = c.q_pix[q];
+        float* o = o_lvl + (size_t)pix * a.pix_stride + (size_t)(i0 * K) * tap_stride;
+        int plane = i0 * K * a.tap_stride * 4;                            // NCHW: byte offset of tap (i, 0)'s plane (uniform)
         float left[K + 1], right[K + 1];
 #pragma unroll
-        for (int j = 0; j <= K; ++j) left[j] = s[j * G::WSX * SST];
+        for (int j = 0; j <= K; ++j) left[j] = s[j * G::WSX * SST] * wl;
         for (int i = i0; i < i1; ++i) {
             s += SST;
 #pragma unroll
             for (int j = 0; j <= K; ++j) right[j] = s[j * G::WSX * SST];
-            float hprev = left[0] + fx * (right[0] - left[0]);
+            float hprev = left[0] + wr * right[0];
 #pragma unroll
             for (int j = 0; j < K; ++j) {
-                const float hcur = left[j + 1] + fx * (right[j + 1] - left[j + 1]);
+                const float hcur = left[j + 1] + wr * right[j + 1];
+                const float v = hprev + fy * (hcur - hprev);
 #ifdef CORR_DEBUG_NOSTORE
                 if (a.scale == 12345.f)
 #endif
-                o[(size_t)j * tap_stride] = (hprev + fy * (hcur - hprev)) * a.scale;    // 1/sqrt(D), once per tap
+                {
+                    if constexpr (NHWC) o[j] = v;
+                    else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), orsrc, pix * 4, plane + j * a.tap_stride * 4, 0);
+                }
                 hprev = hcur;
             }
 #pragma unroll
-            for (int j = 0; j <= K; ++j) left[j] = right[j];
-            o += (size_t)K * tap_stride;
+            for (int j = 0; j <= K; ++j) left[j] = right[j] * wl;
+            o += K;
+            plane += K * a.tap_stride * 4;
         }
     }
 }

@@ -14,8 +14,12 @@
 #define CORR_LOG_CX 4          // target cell: 2^LOG_CX x 2^LOG_CY level-0 pixels
 #define CORR_LOG_CY 3
 #define CORR_SUB 8             // sub-bins per cell: source row mod 8, so a cell's queries come as runs of source pixels, row by row
+#ifndef CORR_LOG_TX
 #define CORR_LOG_TX 2          // super-tile: 2^LOG_TX x 2^LOG_TY cells whose ids are consecutive
-#define CORR_LOG_TY 3
+#endif
+#ifndef CORR_LOG_TY
+#define CORR_LOG_TY 2
+#endif
 #define CORR_TILE_CELLS (1 << (CORR_LOG_TX + CORR_LOG_TY))
 #define CORR_COORD_LIMIT 1048576.0f
 #define CORR_NSTATS 24
@@ -31,7 +35,7 @@ struct CellGrid {
     int tnx, tny;          // super-tiles per axis (grid padded up)
 };
 
-// Cell ids are super-tile major: the cells of a 4 x 8 super-tile (64 x 64 target pixels) are
+// Cell ids are super-tile major: the cells of a 4 x 4 super-tile (64 x 32 target pixels) are
 // consecutive, so work items that run at the same time on one XCD cover a compact 2-D patch of
 // the target image and find each other's window rows and columns in that XCD's L2.
 __host__ __device__ static inline int corr_cell_id(const CellGrid& g, int b, int u, int v) {   // u, v grid-relative
@@ -49,7 +53,9 @@ __host__ __device__ static inline void corr_cell_coords(const CellGrid& g, int i
 // the XCDs in runs of CORR_XCD_RUN consecutive items (neighbouring cells share window rows and columns, so
 // they should share an L2), round robin, so that cheap border regions do not all land on one XCD.  On a grid
 // that is a multiple of 8 * CORR_XCD_RUN workgroups (corr_block_grid) this is a permutation of the grid.
-#define CORR_XCD_RUN 32
+#ifndef CORR_XCD_RUN
+#define CORR_XCD_RUN 16
+#endif
 __host__ __device__ static inline int corr_item_of_workgroup(int w) {
     const int j = w >> 3;
     return ((j / CORR_XCD_RUN) * 8 + (w & 7)) * CORR_XCD_RUN + j % CORR_XCD_RUN;
