@@ -20,7 +20,8 @@ extern "C" {
  *   query_levels     B*H*W*L
  *   null_query_levels  query-levels whose cell window lies wholly outside the level (written as zeros,
  *                      no contraction)
- *   mma_point_queries  sum over items of window points x queries padded to 16: the contraction
+ *   mma_point_queries  sum over items of window points (padded to 16-row blocks) x the query columns the
+ *                      kernel runs (128 per item, 64 for an item of up to 64 queries): the contraction
  *                      work actually issued is 2*D*mma_point_queries flop per bf16 term
  *   used_point_queries sum over items of window points x real queries
  */

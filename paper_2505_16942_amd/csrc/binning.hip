@@ -204,7 +204,9 @@ __global__ __launch_bounds__(256) void bin_stats_kernel(StatArgs a) {
             corr_cell_coords(a.g, cell, &bb, &u, &w);
             u += a.g.u_min; w += a.g.v_min;
             const int items_here = (c + CORR_GROUP - 1) / CORR_GROUP;
-            const int pad_q = (c / CORR_GROUP) * CORR_GROUP + (((c % CORR_GROUP) + 15) & ~15);
+            // columns the block kernel runs MFMAs for: a full group per item, half a group for an item of up to half
+            const int rem = c % CORR_GROUP;
+            const int pad_q = (c / CORR_GROUP) * CORR_GROUP + (rem == 0 ? 0 : rem > CORR_GROUP / 2 ? CORR_GROUP : CORR_GROUP / 2);
 #pragma unroll
             for (int l = 0; l < CORR_MAX_L; ++l) {
                 if (l >= a.L) break;
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(256) void bin_stats_kernel(StatArgs a) {
                 const int wsx = max((1 << CORR_LOG_CX) >> l, 1) + K, wsy = max((1 << CORR_LOG_CY) >> l, 1) + K;
                 const int xs = ((u << CORR_LOG_CX) >> l) - a.r, ys = ((w << CORR_LOG_CY) >> l) - a.r;
                 if (xs + wsx - 1 >= 0 && xs <= a.Wl[l] - 1 && ys + wsy - 1 >= 0 && ys <= a.Hl[l] - 1) {
-                    v[l][0] = items_here; v[l][1] = (long long)wsx * wsy * pad_q;
+                    v[l][0] = items_here; v[l][1] = (long long)((wsx * wsy + 15) & ~15) * pad_q;    // rows in blocks of 16
                     v[l][2] = (long long)wsx * wsy * c; v[l][3] = c;
                 }
             }

@@ -80,7 +80,7 @@ struct BlockArgs {
 
 // S rows are 64 queries + 4 floats of padding: the four row groups a wave writes at once then fall in
 // different banks, and a row read by 64 lanes still covers every bank once
-constexpr int SST = 68;
+constexpr int SST = 68;                                // floats between S rows; 3 * SST < 256: a two-address LDS write reaches rows +1..+3
 #ifndef CORR_LDS_PF
 #define CORR_LDS_PF 3
 #endif
@@ -500,10 +500,10 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
                 unsigned addr = c.lds_base + ((4 * (lane >> 4)) * SST + wave * 16 + (lane & 15)) * 4;
 #pragma unroll
                 for (int b = 0; b < G::NB; ++b) {
-                    asm volatile("ds_write_b32 %0, %1\n\tds_write_b32 %0, %2 offset:%5\n\t"
-                                 "ds_write_b32 %0, %3 offset:%6\n\tds_write_b32 %0, %4 offset:%7"
+                    // two rows per instruction (offsets in dwords: rows are SST floats apart)
+                    asm volatile("ds_write2_b32 %0, %1, %2 offset1:%5\n\tds_write2_b32 %0, %3, %4 offset0:%6 offset1:%7"
                                  :: "v"(addr), "a"(acc[b][h][0]), "a"(acc[b][h][1]), "a"(acc[b][h][2]), "a"(acc[b][h][3]),
-                                    "n"(SST * 4), "n"(2 * SST * 4), "n"(3 * SST * 4) : "memory");
+                                    "n"(SST), "n"(2 * SST), "n"(3 * SST) : "memory");
                     addr += 16 * SST * 4;
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");

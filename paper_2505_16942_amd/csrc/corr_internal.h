@@ -18,7 +18,7 @@
 #define CORR_LOG_TX 2          // super-tile: 2^LOG_TX x 2^LOG_TY cells whose ids are consecutive
 #endif
 #ifndef CORR_LOG_TY
-#define CORR_LOG_TY 2
+#define CORR_LOG_TY 3
 #endif
 #define CORR_TILE_CELLS (1 << (CORR_LOG_TX + CORR_LOG_TY))
 #define CORR_COORD_LIMIT 1048576.0f
@@ -35,7 +35,7 @@ struct CellGrid {
     int tnx, tny;          // super-tiles per axis (grid padded up)
 };
 
-// Cell ids are super-tile major: the cells of a 4 x 4 super-tile (64 x 32 target pixels) are
+// Cell ids are super-tile major: the cells of a 4 x 8 super-tile (64 x 64 target pixels) are
 // consecutive, so work items that run at the same time on one XCD cover a compact 2-D patch of
 // the target image and find each other's window rows and columns in that XCD's L2.
 __host__ __device__ static inline int corr_cell_id(const CellGrid& g, int b, int u, int v) {   // u, v grid-relative
@@ -54,7 +54,7 @@ __host__ __device__ static inline void corr_cell_coords(const CellGrid& g, int i
 // they should share an L2), round robin, so that cheap border regions do not all land on one XCD.  On a grid
 // that is a multiple of 8 * CORR_XCD_RUN workgroups (corr_block_grid) this is a permutation of the grid.
 #ifndef CORR_XCD_RUN
-#define CORR_XCD_RUN 16
+#define CORR_XCD_RUN 32
 #endif
 __host__ __device__ static inline int corr_item_of_workgroup(int w) {
     const int j = w >> 3;

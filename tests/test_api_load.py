@@ -93,9 +93,9 @@ def test_every_work_item_has_exactly_one_workgroup():
         grid, m = binding.corr_debug_item_map(max_items)
         assert grid >= max_items and grid % 8 == 0
         assert np.array_equal(np.sort(m), np.arange(grid)), max_items
-    # consecutive items stay on one XCD (workgroup w runs on XCD w % 8) in runs of 16 (one 4 x 4 super-tile of cells)
+    # consecutive items stay on one XCD (workgroup w runs on XCD w % 8) in runs of 32 (one 4 x 8 super-tile of cells)
     grid, m = binding.corr_debug_item_map(4096)
     xcd_of_item = np.empty(grid, np.int64)
     xcd_of_item[m] = np.arange(grid) % 8
-    assert np.all(xcd_of_item.reshape(-1, 16) == xcd_of_item.reshape(-1, 16)[:, :1])
-    assert np.array_equal(xcd_of_item.reshape(-1, 16)[:8, 0], np.arange(8))
+    assert np.all(xcd_of_item.reshape(-1, 32) == xcd_of_item.reshape(-1, 32)[:, :1])
+    assert np.array_equal(xcd_of_item.reshape(-1, 32)[:8, 0], np.arange(8))
