@@ -123,17 +123,18 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
  * corr_sample for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and same kernels as
  * corr_sample (block mode, bf16x3, NCHW out), but the planning workspace of the lookup (bin
- * counters and offsets, three ints per query, the item list) is not the pyramid's: it is a fixed
+ * counters and offsets, 20 bytes per query, the item list) is not the pyramid's: it is a fixed
  * array of CORR_STATIC_SCRATCH_BYTES that the library's code object holds on every GPU it is loaded
  * on, until the process ends.  The call allocates and frees nothing and only enqueues kernels on
  * `stream`.
  *   limit   : inputs whose workspace exceeds the array return CORR_ERR_TOO_LARGE (it holds
- *             B*H*W up to about 150,000 queries: the 4K-input configuration fits, the 8K one does not).
+ *             B*H*W up to about 190,000 queries: a 270 x 480 map, the 4K-input configuration, needs
+ *             2.7 MB and fits; a 540 x 960 map needs 10.9 MB and does not).
  *   sharing : all calls on one GPU use that GPU's one array, which keeps the previous call's
  *             contents; the call clears the counters it needs at zero itself.  Calls that overlap
  *             on one GPU (different streams, or a graph replay beside an eager call) race.
  */
-#define CORR_STATIC_SCRATCH_BYTES (2u << 20)
+#define CORR_STATIC_SCRATCH_BYTES (4u << 20)
 corr_status corr_sample_static(const float* fmap1, const corr_pyramid* pyr, const float* coords,
                                int B, int H, int W, int D, int L, int r,
                                float* out, void* stream);

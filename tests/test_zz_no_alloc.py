@@ -44,8 +44,14 @@ def test_two_calls_in_a_row_second_smaller_and_the_size_limit():
     b.load_library()
     _case(b, 301, 2, 96, 128, 64, 4, 20.0)      # 24,576 queries: the multi-workgroup planning path
     _case(b, 302, 1, 30, 44, 96, 3, 9.0)        # smaller: one-workgroup planning, other bin layout
-    # beyond the array: refused with its own status, nothing enqueued
     dev = torch.device("cuda:0")
+    # the largest benchmark configuration that fits the array (270 x 480: 2.7 MB of workspace)
+    g = torch.randn((1, 32, 270, 480), device=dev)
+    cc = torch.rand((1, 2, 270, 480), device=dev) * 300.0
+    pyr = b.corr_pyramid_build(g, g, L=4)
+    assert torch.equal(b.corr_sample_static(g, pyr, cc), b.corr_sample(g, pyr, cc))
+    pyr.destroy()
+    # beyond the array: refused with its own status, nothing enqueued
     f = torch.zeros((1, 32, 540, 960), device=dev)
     pyr = b.corr_pyramid_build(f, f, L=4)
     c = torch.zeros((1, 2, 540, 960), device=dev)
