@@ -78,6 +78,14 @@ corr_status corr_copy_f32(float* dst, const float* src, size_t n, void* stream);
 corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32_t* items, size_t items_cap,
                                  int32_t* perm, size_t perm_cap, void* stream);
 /*
+ * Test hook (process-wide): block-mode lookups of up to `max_queries` queries (B*H*W) are launched with the
+ * kernel that can run an item's levels in workgroups of their own (it does so while the item count is small
+ * enough: four ways up to 64 items, two ways up to 640, else all levels in one workgroup).  0 = never (the
+ * one-workgroup-per-item kernel that large inputs take), -1 restores the default (65536), -2 / -4 = always two / four ways, whatever the size.  All forms give the same bits.
+ * Returns the previous setting.  Not synchronised with lookups in flight on other threads.
+ */
+int corr_debug_set_level_split(int max_queries);
+/*
  * Test hook (host only, no GPU work): the block kernel's launch grid for a workspace that can hold
  * `max_items` work items, and which item each workgroup takes: map[w] for w < *grid.  Pass map = NULL
  * to get the grid size alone; CORR_ERR_INVALID_ARG if map_cap < *grid.

@@ -33,6 +33,7 @@ EXPORTS = [
 BENCH_EXPORTS = [
     "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry", "corr_copy_f32",
     "corr_debug_read_plan", "corr_debug_cell_coords", "corr_debug_read_level", "corr_debug_item_map",
+    "corr_debug_set_level_split",
 ]
 
 
@@ -104,6 +105,8 @@ def load_library():
     lib.corr_debug_cell_coords.restype = ci
     lib.corr_debug_item_map.argtypes = [ci, ctypes.POINTER(ctypes.c_int32), ctypes.c_size_t, ctypes.POINTER(ci)]
     lib.corr_debug_item_map.restype = ci
+    lib.corr_debug_set_level_split.argtypes = [ci]
+    lib.corr_debug_set_level_split.restype = ci
     lib.corr_debug_read_level.argtypes = [vp, cu, ci, ctypes.POINTER(ctypes.c_float), vp]
     lib.corr_debug_read_level.restype = ci
     lib.corr_status_string.argtypes = [ci]
@@ -285,6 +288,13 @@ def corr_debug_read_plan(pyramid: Pyramid):
     if st != CORR_OK:
         raise CorrError(st, "corr_debug_read_plan")
     return items[:counts[0]].copy(), perm[:counts[1]].copy()
+
+
+def corr_debug_set_level_split(max_queries: int) -> int:
+    """Block mode on inputs of up to `max_queries` queries is launched with the kernel that can run an item's
+    levels in workgroups of their own; 0 = never, -1 = the default, -2 / -4 = always two / four ways.
+    Returns the previous setting."""
+    return int(load_library().corr_debug_set_level_split(int(max_queries)))
 
 
 def corr_debug_item_map(max_items: int):

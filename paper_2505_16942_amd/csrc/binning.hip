@@ -26,7 +26,7 @@
 namespace {
 
 constexpr int SCAN_T = 1024;          // threads of a workgroup that scans
-constexpr int SMALL_MAX_Q = 8;        // queries per thread of the one-workgroup path
+constexpr int SMALL_MAX_Q = 2;        // queries per thread of the one-workgroup path
 
 struct BinArgs {
     const float* coords;   // [B][2][H*W]
@@ -60,18 +60,29 @@ __device__ __forceinline__ int query_bin(const BinArgs& a, int b, int p) {
 
 // Neighbouring pixels mostly fall in the same bin: one atomic per run of equal bins among
 // consecutive lanes, the rest of the run takes offsets.  Every lane of the wave must call this.
-__device__ __forceinline__ int take_rank(int* bin_count, int bin) {
+// In two halves, so that a caller with several queries per thread can have all its atomics in
+// flight before it needs the first result.
+struct RankTicket { int base, head_lane; };
+__device__ __forceinline__ RankTicket take_rank_issue(int* bin_count, int bin) {
     const int lane = threadIdx.x & 63;
     const int prev = __shfl_up(bin, 1, 64);
     const bool head = (lane == 0) || (bin != prev);
     const unsigned long long heads = __ballot(head);
     const unsigned long long upto = (lane == 63) ? ~0ull : ((2ull << lane) - 1ull);
-    const int head_lane = 63 - __clzll((long long)(heads & upto));
+    RankTicket t;
+    t.head_lane = 63 - __clzll((long long)(heads & upto));
     const unsigned long long above = heads & ~upto;
     const int next = above ? (__ffsll((long long)above) - 1) : 64;
-    int base = 0;
-    if (head && bin >= 0) base = atomicAdd(&bin_count[bin], next - lane);
-    return __shfl(base, head_lane, 64) + (lane - head_lane);
+    t.base = 0;
+    if (head && bin >= 0) t.base = atomicAdd(&bin_count[bin], next - lane);
+    return t;
+}
+__device__ __forceinline__ int take_rank_finish(const RankTicket& t) {
+    const int lane = threadIdx.x & 63;
+    return __shfl(t.base, t.head_lane, 64) + (lane - t.head_lane);
+}
+__device__ __forceinline__ int take_rank(int* bin_count, int bin) {
+    return take_rank_finish(take_rank_issue(bin_count, bin));
 }
 
 // One workgroup of SCAN_T threads: exclusive scan of the bin counts (query offsets) and of the
@@ -161,13 +172,21 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(BinArgs a) {
 __global__ __launch_bounds__(SCAN_T) void bin_small_kernel(BinArgs a) {
     const int BN = a.B * a.HW;
     int bin[SMALL_MAX_Q], rank[SMALL_MAX_Q];
+    RankTicket ticket[SMALL_MAX_Q];
 #pragma unroll
     for (int k = 0; k < SMALL_MAX_Q; ++k) {
         const int q = k * SCAN_T + threadIdx.x;
         bin[k] = -1;
         if (q < BN) { const int b = q / a.HW; bin[k] = query_bin(a, b, q - b * a.HW); }
-        rank[k] = (k * SCAN_T < BN) ? take_rank(a.ws.bin_count, bin[k]) : 0;     // uniform condition
     }
+    // all of a thread's atomics are in flight before the first result is used
+#pragma unroll
+    for (int k = 0; k < SMALL_MAX_Q; ++k) {
+        ticket[k].base = 0; ticket[k].head_lane = 0;
+        if (k * SCAN_T < BN) ticket[k] = take_rank_issue(a.ws.bin_count, bin[k]);        // uniform condition
+    }
+#pragma unroll
+    for (int k = 0; k < SMALL_MAX_Q; ++k) rank[k] = (k * SCAN_T < BN) ? take_rank_finish(ticket[k]) : 0;
     __syncthreads();                  // every atomic of this workgroup has returned
     scan_cells(a.ws);
     __syncthreads();                  // the offsets were written by threads of this workgroup

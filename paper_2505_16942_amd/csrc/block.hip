@@ -73,6 +73,7 @@ struct BlockArgs {
     int rec;                             // elements per pixel record: 64 (hi + lo) or 32 (hi only)
     CellGrid g;
     float scale;
+    int force_ways;                      // block_level_kernel: 0 = decide from the item count, else 2 or 4
 #ifdef CORR_TRACE
     long long* trace;                    // [items][16] timestamps (debug builds)
 #endif
@@ -207,7 +208,7 @@ __device__ __forceinline__ void issue_unit(const BlockArgs& a, const ItemCtx& c,
     rs[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)pb);
     rs[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(pb >> 32));
     rs[2] = __builtin_amdgcn_readfirstlane(real ? c.rsrc[2] : 0);
-    rs[3] = c.rsrc[3];
+    rs[3] = __builtin_amdgcn_readfirstlane(c.rsrc[3]);
 #pragma unroll
     for (int it = 0; it < G::ITERS; ++it)
         if (it >= it0 && it < it1)                                // constants once the callers' loops are unrolled
@@ -453,7 +454,7 @@ __device__ __forceinline__ void begin_level(const BlockArgs& a, const ItemCtx& c
 
 // One level of one work item.  On entry `pl` holds the staging plan and units 0 .. pl.pre-1 are
 // in flight; before its own epilogue the level plans the next one and issues its first units.
-template <int LVL, bool THREE, bool BIGD, bool NHWC, bool TWO, class NextPlan>
+template <int LVL, bool THREE, bool BIGD, bool NHWC, bool TWO, class NextPlan, bool NEXT = true>
 __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
                                            bf16x8 (&qhi)[2][NCMAX], bf16x8 (&qlo)[2][NCMAX],
                                            Plan<LVL, THREE>& pl, NextPlan& nx) {
@@ -461,7 +462,7 @@ __device__ __forceinline__ void level_pass(const BlockArgs& a, const ItemCtx& c,
     float* S = reinterpret_cast<float*>(smem);               // [ROWS][64], aliases the ring
     const int lane = c.lane, wave = c.wave;
     auto begin_next = [&]() {
-        if constexpr (LVL + 1 < CORR_MAX_L) begin_level<LVL + 1, THREE>(a, c, nx);
+        if constexpr (NEXT && LVL + 1 < CORR_MAX_L) begin_level<LVL + 1, THREE>(a, c, nx);
     };
     if (!pl.touches) {                                       // uniform: a window that is all padding gives zero taps
         begin_next();
@@ -530,19 +531,19 @@ __device__ __forceinline__ void run_levels(const BlockArgs& a, const ItemCtx& c,
     if (a.L > 3) level_pass<3, THREE, BIGD, NHWC, TWO>(a, c, smem, qhi, qlo, p3, p3);
 }
 
-template <bool THREE, bool BIGD, bool NHWC>
-__global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
+// What every workgroup sets up first: its item (XCD-aware choice; the grid covers the largest possible item
+// count and the tail exits), the thread's indices, the LDS addresses, the buffer resource of the pyramid.
+// Returns false when there is no item for this workgroup.
+template <bool SPREAD = false>
+__device__ __forceinline__ bool init_item(const BlockArgs& a, unsigned char* smem, ItemCtx& c, int4& item) {
     int* q_pix = reinterpret_cast<int*>(smem + LDS_DATA);
     float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP);
-    float* q_cy = q_cx + CORR_GROUP;
-
-    // XCD-aware item choice; the grid covers the largest possible item count, the tail exits here
     const int n_items = *a.n_items;
-    const int k = corr_item_of_workgroup(blockIdx.x);
-    if (k >= n_items) return;
-    const int4 item = a.items[k];
-    ItemCtx c;
+    // SPREAD: consecutive items on different XCDs (workgroup w runs on XCD w % 8).  With few items the runs
+    // of the XCD-aware choice would put them all on one or two XCDs and leave the other compute units idle.
+    const int k = SPREAD ? (int)blockIdx.x : corr_item_of_workgroup(blockIdx.x);
+    if (k >= n_items) return false;
+    item = a.items[k];
     c.item = k;
     c.tid = threadIdx.x; c.lane = c.tid & 63;
     // the wave index as a scalar: branches on it must be scalar branches, or the compiler copies every
@@ -551,21 +552,17 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     c.n = item.z;
     corr_cell_coords(a.g, item.x, &c.b, &c.u, &c.v);
     c.u += a.g.u_min; c.v += a.g.v_min;
-    c.q_pix = q_pix; c.q_cx = q_cx; c.q_cy = q_cy;
+    c.q_pix = q_pix; c.q_cx = q_cx; c.q_cy = q_cx + CORR_GROUP;
     c.lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     c.lds_wave = __builtin_amdgcn_readfirstlane(c.lds_base + c.wave * 1024);
     const uint64_t base = reinterpret_cast<uint64_t>(a.f2s);
     c.rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)base);
     c.rsrc[1] = __builtin_amdgcn_readfirstlane((int)((base >> 32) & 0xffffu));
     c.rsrc[2] = __builtin_amdgcn_readfirstlane((int)a.f2_plane_bytes); c.rsrc[3] = 0x00020000;
-
-    TRACE(0);
-    // level 0's first unit starts to move before anything else
-    Plan<0, THREE> p0;
-    p0.pre = 0;
-    p0.touches = window_touches<0, THREE>(a, c);
-    if (p0.touches) { plan<0, THREE>(a, c, p0.voff); issue_units<0, THREE, 0, 1>(a, c, p0); }
-
+    return true;
+}
+// the item's query records (pixel, x, y) from the sorted list into LDS
+__device__ __forceinline__ void load_records(const BlockArgs& a, const ItemCtx& c, const int4& item) {
     if (c.tid < CORR_GROUP) {
         int pix = -1;
         float2 xy = make_float2(0.f, 0.f);
@@ -573,9 +570,27 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
             pix = a.perm[item.y + c.tid] - c.b * a.HW;
             xy = a.sorted_c[item.y + c.tid];
         }
-        q_pix[c.tid] = pix; q_cx[c.tid] = xy.x; q_cy[c.tid] = xy.y;
+        const_cast<int*>(c.q_pix)[c.tid] = pix;
+        const_cast<float*>(c.q_cx)[c.tid] = xy.x;
+        const_cast<float*>(c.q_cy)[c.tid] = xy.y;
     }
     __syncthreads();
+}
+
+template <bool THREE, bool BIGD, bool NHWC>
+__global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    ItemCtx c;
+    int4 item;
+    if (!init_item(a, smem, c, item)) return;
+
+    TRACE(0);
+    // level 0's first unit starts to move before anything else
+    Plan<0, THREE> p0;
+    p0.pre = 0;
+    p0.touches = window_touches<0, THREE>(a, c);
+    if (p0.touches) { plan<0, THREE>(a, c, p0.voff); issue_units<0, THREE, 0, 1>(a, c, p0); }
+    load_records(a, c, item);
 
     bf16x8 qhi[2][NCMAX], qlo[2][NCMAX];
     load_queries<THREE>(a, c, 0, qhi, qlo);        // ends with a full wait: unit 0 is in as well
@@ -587,13 +602,72 @@ __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     else run_levels<THREE, BIGD, NHWC, false>(a, c, smem, qhi, qlo, p0);
 }
 
+// Small inputs: several workgroups per item, each taking a range of levels (blockIdx.y).  A map of a few
+// thousand queries has fewer items than the chip has compute units, and a lookup's time is one item's latency;
+// with the levels side by side that latency is the longest range's instead of the sum of all levels.
+template <int LVL, int HI, bool THREE, bool BIGD, bool NHWC, bool TWO>
+__device__ __forceinline__ void level_chain(const BlockArgs& a, const ItemCtx& c, unsigned char* smem,
+                                            bf16x8 (&qhi)[2][NCMAX], bf16x8 (&qlo)[2][NCMAX], Plan<LVL, THREE>& pl) {
+    if constexpr (LVL + 1 < HI) {
+        Plan<LVL + 1, THREE> nx;                   // planned, and its first units issued, under this level's epilogue
+        level_pass<LVL, THREE, BIGD, NHWC, TWO, Plan<LVL + 1, THREE>, true>(a, c, smem, qhi, qlo, pl, nx);
+        if (a.L > LVL + 1) level_chain<LVL + 1, HI, THREE, BIGD, NHWC, TWO>(a, c, smem, qhi, qlo, nx);
+    } else {
+        level_pass<LVL, THREE, BIGD, NHWC, TWO, Plan<LVL, THREE>, false>(a, c, smem, qhi, qlo, pl, pl);
+    }
+}
+template <int LO, int HI, bool THREE, bool BIGD, bool NHWC>
+__device__ __forceinline__ void level_range(const BlockArgs& a, const ItemCtx& c, const int4& item, unsigned char* smem) {
+    if (LO >= a.L) return;                         // uniform: this pyramid has no such level
+    Plan<LO, THREE> pl;
+    begin_level<LO, THREE>(a, c, pl);              // the plan and the level's first units, before anything else
+    load_records(a, c, item);
+    bf16x8 qhi[2][NCMAX], qlo[2][NCMAX];
+    load_queries<THREE>(a, c, 0, qhi, qlo);
+    if (c.n > 64) level_chain<LO, HI, THREE, BIGD, NHWC, true>(a, c, smem, qhi, qlo, pl);
+    else level_chain<LO, HI, THREE, BIGD, NHWC, false>(a, c, smem, qhi, qlo, pl);
+}
+// Launched with gridDim.y = CORR_MAX_L.  How many of an item's workgroups work is decided here, from the item
+// count the planning pass left: one per level while that many workgroups still fit the chip's compute units
+// at once; two (level 0 | the other levels) up to 2.5 items per compute unit, where the finer grain still
+// buys more balance than the second start costs (measured: 372 items 99 -> 90 us); else one that runs all
+// levels.  The others exit.
+template <bool THREE, bool BIGD, bool NHWC>
+__global__ __launch_bounds__(NT, 1) void block_level_kernel(BlockArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    ItemCtx c;
+    int4 item;
+    if (!init_item<true>(a, smem, c, item)) return;
+    const int n_items = *a.n_items;
+    const int ways = a.force_ways ? a.force_ways : CORR_MAX_L * n_items <= CORR_NUM_CU ? CORR_MAX_L : 2 * n_items <= 5 * CORR_NUM_CU ? 2 : 1;
+    const int y = blockIdx.y;                      // uniform, like everything above
+    if (y >= ways) return;
+    if (ways == 1) {
+        level_range<0, CORR_MAX_L, THREE, BIGD, NHWC>(a, c, item, smem);
+    } else if (ways == 2) {
+        if (y == 0) level_range<0, 1, THREE, BIGD, NHWC>(a, c, item, smem);
+        else level_range<1, CORR_MAX_L, THREE, BIGD, NHWC>(a, c, item, smem);
+    } else {
+        switch (y) {
+            case 0: level_range<0, 1, THREE, BIGD, NHWC>(a, c, item, smem); break;
+            case 1: level_range<1, 2, THREE, BIGD, NHWC>(a, c, item, smem); break;
+            case 2: level_range<2, 3, THREE, BIGD, NHWC>(a, c, item, smem); break;
+            default: level_range<3, 4, THREE, BIGD, NHWC>(a, c, item, smem); break;
+        }
+    }
+}
+
 template <bool THREE, bool BIGD, bool NHWC>
 hipError_t launch_items(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s) {
     auto kfn = block_kernel<THREE, BIGD, NHWC>;
+    auto kfn_levels = block_level_kernel<THREE, BIGD, NHWC>;
     // once per instantiation and process (initialisation of a local static is thread-safe)
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    static const hipError_t attr_levels = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn_levels),
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (attr != hipSuccess) return attr;
+    if (attr_levels != hipSuccess) return attr_levels;
     BlockArgs a;
     a.f1s = p->f1_split; a.f2s = p->f2_split; a.perm = ws.perm; a.sorted_c = ws.sorted_c; a.items = ws.items;
     a.n_items = ws.n_items; a.out = q.out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L;
@@ -609,7 +683,13 @@ hipError_t launch_items(const corr_pyramid* p, const BinWs& ws, const LookupArgs
     a.trace = g_corr_trace;
 #endif
     const int grid = corr_block_grid(ws.max_items);
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), LDS_BYTES, s, a);
+    // Small inputs may have fewer items than the chip has compute units; then the levels of an item run side by
+    // side in workgroups of their own.  The kernel that can do that is launched up to split_levels_max queries
+    // and decides from the item count (negative settings are test settings: -2 / -4 = always 2 / 4 ways).
+    const long long BN = (long long)p->B * p->H * p->W, lim = q.split_levels_max;
+    a.force_ways = lim == -2 ? 2 : lim == -4 ? CORR_MAX_L : 0;
+    if (BN <= lim || a.force_ways) hipLaunchKernelGGL(kfn_levels, dim3(grid, CORR_MAX_L), dim3(NT), LDS_BYTES, s, a);
+    else hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), LDS_BYTES, s, a);
     return hipGetLastError();
 }
 

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include "corr_internal.h"
+#include <atomic>
 
 namespace {
 
@@ -126,6 +127,9 @@ struct Profiler {
     long long dropped = 0;
     hipEvent_t* ev = nullptr;      // [PROF_LOOKUPS][3]
 } g_prof;
+
+// process-wide test knob (corr_debug_set_level_split)
+std::atomic<int> g_split_levels_max{CORR_SPLIT_LEVELS_MAX_QUERIES};
 
 hipError_t launch_block(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s) {
     return q.r == 1 ? launch_block_r1(p, ws, q, s)
@@ -305,6 +309,7 @@ corr_status corr_sample_layout(corr_mode mode, corr_precision prec, corr_out_lay
     hipError_t e = hipSuccess;
     LookupArgs q;
     q.coords = coords; q.out = out; q.r = r; q.nhwc = layout == CORR_OUT_NHWC; q.prec = (int)prec;
+    q.split_levels_max = g_split_levels_max.load();
     switch (mode) {
         case CORR_MODE_BLOCK: {
             if (prec != CORR_PREC_BF16X3 && prec != CORR_PREC_BF16) return CORR_ERR_INVALID_ARG;
@@ -370,6 +375,7 @@ corr_status corr_sample_static(const float* fmap1, const corr_pyramid* pyr, cons
     if (e == hipSuccess) e = launch_fill_i32(ws.n_items, 0, 4, s);
     LookupArgs q;
     q.coords = coords; q.out = out; q.r = r; q.nhwc = 0; q.prec = (int)CORR_PREC_BF16X3;
+    q.split_levels_max = g_split_levels_max.load();
     if (e == hipSuccess) e = enqueue_block_lookup(pyr, ws, q, s);
     return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
@@ -459,6 +465,10 @@ corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32
     if (hn[1] > 0 && hipMemcpyAsync(perm, pyr->ws.perm, (size_t)hn[1] * 4, hipMemcpyDeviceToHost, s) != hipSuccess)
         return CORR_ERR_HIP;
     return hipStreamSynchronize(s) == hipSuccess ? CORR_OK : CORR_ERR_HIP;
+}
+
+int corr_debug_set_level_split(int max_queries) {
+    return g_split_levels_max.exchange(max_queries == -1 ? CORR_SPLIT_LEVELS_MAX_QUERIES : max_queries);
 }
 
 corr_status corr_debug_item_map(int max_items, int32_t* map, size_t map_cap, int* grid) {

@@ -21,6 +21,12 @@
 #define CORR_LOG_TY 3
 #endif
 #define CORR_TILE_CELLS (1 << (CORR_LOG_TX + CORR_LOG_TY))
+#ifndef CORR_SPLIT_LEVELS_MAX_QUERIES
+#define CORR_SPLIT_LEVELS_MAX_QUERIES 65536   // inputs up to this many queries may run an item's levels in workgroups of their own
+#endif
+#ifndef CORR_NUM_CU
+#define CORR_NUM_CU 256                       // compute units of the chip this is written for
+#endif
 #define CORR_COORD_LIMIT 1048576.0f
 #define CORR_NSTATS 24
 
@@ -160,6 +166,7 @@ struct LookupArgs {
     int r;          // radius of this lookup
     int nhwc;       // layout of out
     int prec;       // corr_precision
+    int split_levels_max;   // block mode: inputs of up to this many queries run one workgroup per (item, level)
 };
 // Where tap t of pixel p of batch item b goes in `out`: b * taps * HW + t * tap_stride + p * pix_stride,
 // with (tap_stride, pix_stride) = (HW, 1) for NCHW and (1, taps) for NHWC.

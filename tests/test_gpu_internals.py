@@ -74,13 +74,13 @@ def _host_rule(c, H, W, L, geom0):
     return ok, u, v
 
 
-@pytest.mark.parametrize("case", [(2, 40, 60, 4, 9.0), (1, 100, 130, 4, 30.0), (3, 64, 48, 3, 3.0)])
+@pytest.mark.parametrize("case", [(2, 24, 40, 4, 9.0), (2, 40, 60, 4, 9.0), (1, 100, 130, 4, 30.0), (3, 64, 48, 3, 3.0)])
 def test_binning_workspace_against_the_rule(case):
     """What the count / scan / scatter kernels leave behind, read back and checked against the rule
     evaluated on the host: every binned query is listed exactly once, in an item of the cell the
     rule gives it; queries the rule leaves out are not listed; items partition the list, hold 1..128
     queries, a cell's items are full except its last; inside a cell queries come by source row mod 8.
-    The first case takes the single-workgroup path (at most 8192 queries), the others the
+    The first case takes the single-workgroup path (at most 2048 queries), the others the
     count + scatter path."""
     B, H, W, L, fr = case
     b = _binding()

@@ -23,6 +23,21 @@ def _binding():
     return binding
 
 
+FORMS = {"one workgroup per level": -4, "two workgroups per item": -2, "decided by item count": 1 << 30, "one workgroup per item": 0}
+
+
+@pytest.fixture(autouse=True, params=list(FORMS))
+def block_kernel_form(request):
+    """Every test of this file runs four times: small inputs take the block kernel with one workgroup per
+    (item, level) or two per item, decided by the item count; large ones one workgroup per item.  Forcing each form in turn covers the
+    edge cases of all of them (ragged maps, missing levels, null queries, D > 256, r < 4) at sizes the oracle
+    handles in seconds."""
+    b = _binding()
+    prev = b.corr_debug_set_level_split(FORMS[request.param])
+    yield request.param
+    b.corr_debug_set_level_split(prev)
+
+
 def _run(f1, f2, c, L, r, mode, prec=0, reps=3):
     b = _binding()
     dev = torch.device("cuda:0")
@@ -243,6 +258,21 @@ def test_other_radii_block_mode_four_levels_far_motion_and_layouts(r):
     ocl = torch.full((B, H, W, L * K * K), float("nan"), dtype=torch.float32, device=dev)
     b.corr_sample(t1, pyr, tc, r=r, out=ocl, layout=b.CORR_OUT_NHWC)
     assert torch.equal(ocl.permute(0, 3, 1, 2), out)
+    pyr.destroy()
+
+
+def test_both_block_kernel_forms_give_the_same_bits():
+    b = _binding()
+    dev = torch.device("cuda:0")
+    f1, f2, c = synth.small_case(55, 2, 40, 56, 96, flow_range=15.0)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    pyr = b.corr_pyramid_build(t1, t2, L=4)
+    prev = b.corr_debug_set_level_split(0)
+    fused = b.corr_sample(t1, pyr, tc)
+    for form, limit in FORMS.items():
+        b.corr_debug_set_level_split(limit)
+        assert torch.equal(b.corr_sample(t1, pyr, tc), fused), form
+    b.corr_debug_set_level_split(prev)
     pyr.destroy()
 
 
