@@ -80,8 +80,8 @@ corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32
 /*
  * Test hook (process-wide): block-mode lookups of up to `max_queries` queries (B*H*W) are launched with the
  * kernel that can run an item's levels in workgroups of their own (it does so while the item count is small
- * enough: four ways up to 64 items, two ways up to 640, else all levels in one workgroup).  0 = never (the
- * one-workgroup-per-item kernel that large inputs take), -1 restores the default (65536), -2 / -4 = always two / four ways, whatever the size.  All forms give the same bits.
+ * enough: four ways up to 64 items, two ways up to 384, else all levels in one workgroup).  0 = never (the
+ * one-workgroup-per-item kernel that large inputs take), -1 restores the default (32000), -2 / -4 = always two / four ways, whatever the size.  All forms give the same bits.
  * Returns the previous setting.  Not synchronised with lookups in flight on other threads.
  */
 int corr_debug_set_level_split(int max_queries);

@@ -629,7 +629,7 @@ __device__ __forceinline__ void level_range(const BlockArgs& a, const ItemCtx& c
 }
 // Launched with gridDim.y = CORR_MAX_L.  How many of an item's workgroups work is decided here, from the item
 // count the planning pass left: one per level while that many workgroups still fit the chip's compute units
-// at once; two (level 0 | the other levels) up to 2.5 items per compute unit, where the finer grain still
+// at once; two (level 0 | the other levels) up to 1.5 items per compute unit, where the finer grain still
 // buys more balance than the second start costs (measured: 372 items 99 -> 90 us); else one that runs all
 // levels.  The others exit.
 template <bool THREE, bool BIGD, bool NHWC>
@@ -639,7 +639,7 @@ __global__ __launch_bounds__(NT, 1) void block_level_kernel(BlockArgs a) {
     int4 item;
     if (!init_item<true>(a, smem, c, item)) return;
     const int n_items = *a.n_items;
-    const int ways = a.force_ways ? a.force_ways : CORR_MAX_L * n_items <= CORR_NUM_CU ? CORR_MAX_L : 2 * n_items <= 5 * CORR_NUM_CU ? 2 : 1;
+    const int ways = a.force_ways ? a.force_ways : CORR_MAX_L * n_items <= CORR_NUM_CU ? CORR_MAX_L : 2 * n_items <= 3 * CORR_NUM_CU ? 2 : 1;
     const int y = blockIdx.y;                      // uniform, like everything above
     if (y >= ways) return;
     if (ways == 1) {

@@ -22,7 +22,7 @@
 #endif
 #define CORR_TILE_CELLS (1 << (CORR_LOG_TX + CORR_LOG_TY))
 #ifndef CORR_SPLIT_LEVELS_MAX_QUERIES
-#define CORR_SPLIT_LEVELS_MAX_QUERIES 65536   // inputs up to this many queries may run an item's levels in workgroups of their own
+#define CORR_SPLIT_LEVELS_MAX_QUERIES 32000   // inputs up to this many queries may run an item's levels in workgroups of their own
 #endif
 #ifndef CORR_NUM_CU
 #define CORR_NUM_CU 256                       // compute units of the chip this is written for
