@@ -14,6 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "corr_oracle.c")
+_SRC_BACKWARD = os.path.join(_HERE, "corr_oracle_backward.c")
 _LIB = os.path.join(_HERE, "libcorr_oracle.so")
 _lib = None
 # The mutation test loads deliberately broken builds of the oracle through this variable to show
@@ -23,10 +24,11 @@ _OVERRIDE = os.environ.get("CORR_ORACLE_LIB_OVERRIDE")
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (fp64, OpenMP over queries)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BACKWARD))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
-                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+                               "-ffp-contract=off", "-o", tmp, _SRC, _SRC_BACKWARD, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -51,6 +53,9 @@ def _load():
         lib.corr_oracle_lookup_points.argtypes = [f32p, f32p, f32p, ci, ci, ci, ci, ci, ci,
                                                   i64p, ctypes.c_long, f64p]
         lib.corr_oracle_lookup_points.restype = ci
+        if hasattr(lib, "corr_oracle_backward"):          # absent from the mutation test's single-file builds
+            lib.corr_oracle_backward.argtypes = [f32p, f32p, f32p, f64p, ci, ci, ci, ci, ci, ci, f64p, f64p]
+            lib.corr_oracle_backward.restype = ci
         _lib = lib
     return _lib
 
@@ -115,3 +120,18 @@ def lookup_points(fmap1, fmap2, coords, flat_idx, L: int = 4, r: int = 4) -> np.
     if rc:
         raise RuntimeError("corr_oracle_lookup_points failed: %d" % rc)
     return vals
+
+
+def backward(fmap1, fmap2, coords, d_out, L: int = 4, r: int = 4):
+    """Gradients of sum(d_out * lookup) with respect to fmap1 and fmap2 (coordinates are constants):
+    two fp64 arrays [B, D, H, W]."""
+    f1, f2, c, B, D, H, W = _prep(fmap1, fmap2, coords)
+    K = 2 * r + 1
+    g = np.ascontiguousarray(d_out, dtype=np.float64)
+    assert g.shape == (B, L * K * K, H, W)
+    d1 = np.empty((B, D, H, W), dtype=np.float64)
+    d2 = np.empty((B, D, H, W), dtype=np.float64)
+    rc = _load().corr_oracle_backward(f1, f2, c, g, B, H, W, D, L, r, d1, d2)
+    if rc:
+        raise RuntimeError("corr_oracle_backward failed: %d" % rc)
+    return d1, d2

@@ -67,3 +67,38 @@ def test_the_unmodified_oracle_passes_through_the_same_route(tmp_path):
                           os.path.join(ROOT, "tests", "test_oracle_pins.py")],
                          cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
     assert run.returncode == 0, run.stdout[-2000:]
+
+
+# ---- the gradient oracle (oracle/corr_oracle_backward.c), against tests/test_oracle_backward_pins.py
+SRC_BACKWARD = os.path.join(ROOT, "oracle", "corr_oracle_backward.c")
+BACKWARD_MUTANTS = [
+    ("corner weights of x and y swapped", "const double w = (cxi ? wx : 1.0 - wx) * (cyi ? wy : 1.0 - wy);",
+     "const double w = (cxi ? wy : 1.0 - wy) * (cyi ? wx : 1.0 - wx);"),
+    ("pooling adjoint spreads with 1/2", "const double t = 0.25 * dlev[l]", "const double t = 0.5 * dlev[l]"),
+    ("pooling adjoint reaches one pixel only", "for (int a2 = 0; a2 < 2; ++a2)", "for (int a2 = 0; a2 < 1; ++a2)"),
+    ("1/sqrt(D) dropped", "const double gw = g * w * scale;", "const double gw = g * w;"),
+    ("gradient of fmap1 misses the level's features", "+= gw * lev[l][q + d];", "+= gw * lev[0][q + d];"),
+    ("corners on the last column skipped",
+     "if (u < 0 || v < 0 || u >= Wl[l] || v >= Hl[l]) continue;     /* zero padding: no dependence */",
+     "if (u < 0 || v < 0 || u >= Wl[l] - 1 || v >= Hl[l]) continue;"),
+    ("tap offsets swapped", "const double sx = cx * ldexp(1.0, -l) + (double)(i - r);\n"
+     "                            const double sy = cy * ldexp(1.0, -l) + (double)(j - r);",
+     "const double sx = cx * ldexp(1.0, -l) + (double)(j - r);\n"
+     "                            const double sy = cy * ldexp(1.0, -l) + (double)(i - r);"),
+]
+
+@pytest.mark.parametrize("name,old,new", BACKWARD_MUTANTS, ids=[m[0] for m in BACKWARD_MUTANTS])
+def test_backward_pins_reject_a_planted_mistake(tmp_path, name, old, new):
+    src = open(SRC_BACKWARD).read()
+    assert src.count(old) == 1, "the oracle source no longer contains the text this case edits"
+    mutant_c = tmp_path / "mutant_backward.c"
+    mutant_c.write_text(src.replace(old, new))
+    lib = tmp_path / "libmutant.so"
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-ffp-contract=off",
+                           "-o", str(lib), SRC, str(mutant_c), "-lm"])
+    env = dict(os.environ, CORR_ORACLE_LIB_OVERRIDE=str(lib), OMP_NUM_THREADS="4")
+    run = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                          os.path.join(ROOT, "tests", "test_oracle_backward_pins.py")],
+                         cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+    assert run.returncode == 1, "no pin failed for: %s\n%s" % (name, run.stdout[-2000:])
+    assert "failed" in run.stdout
