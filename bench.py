@@ -28,6 +28,56 @@ def kernel_source_sha() -> str:
     return sha()
 
 
+def bench_backward(args, cb, synth, torch, np) -> int:
+    """The gradient entry point: `value` = tap gradients (queries x L x 81) taken back per second."""
+    dev = torch.device("cuda:0")
+    cfg = synth.config(args.config)
+    B, H, W, D, L, r = cfg["B"], cfg["H"], cfg["W"], cfg["D"], cfg["L"], cfg["r"]
+    K = 2 * r + 1
+    N = H * W
+    f1, f2 = synth.features(cfg)
+    c = synth.coords(cfg, 0)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg["seed"])
+    d_out = torch.randn((B, L * K * K, H, W), device=dev, generator=gen)
+    pyr = cb.corr_pyramid_build(t1, t2, L=L, reps=cb.CORR_REP_F32)
+    ws = torch.empty(cb.corr_backward_workspace_bytes(B, H, W, D, L) // 4, device=dev)
+    g1 = torch.empty_like(t1)
+    g2 = torch.empty_like(t1)
+    for _ in range(max(args.warmup, 1)):
+        cb.corr_sample_backward(pyr, tc, d_out, r=r, d_fmap1=g1, d_fmap2=g2, workspace=ws)
+    torch.cuda.synchronize()
+    tb = time.perf_counter()
+    for _ in range(args.steps):
+        cb.corr_sample_backward(pyr, tc, d_out, r=r, d_fmap1=g1, d_fmap2=g2, workspace=ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - tb) / args.steps
+    taps = B * N * L * K * K
+    npyr = sum((H >> l) * (W >> l) for l in range(L))
+    # algorithmic HBM bytes: d_out, fmap1 and every pyramid pixel (fp32) read once, both gradients written once
+    bytes_alg = B * (taps // B * 4 + N * D * 4 + npyr * D * 4 + N * 8 + 2 * N * D * 4)
+    # what bounds this form: one float atomic per (query-level, footprint point inside the level, channel)
+    atomics = float(B * N * L * (K + 1) ** 2 * D)
+    gbs = bytes_alg / dt / 1e9
+    result = {
+        "metric": "correlation lookup gradient, tap gradients/s (queries x L x 81 taps)", "value": taps / dt,
+        "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: B=%d fmap [%d,%d,%d,%d] L=%d r=%d; step = one corr_sample_backward"
+                               % (args.config, B, B, D, H, W, L, r), "seed": cfg["seed"]},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                     "kernel": "bwd_query_kernel (one wave per query, float atomics into the level gradients)",
+                     "algorithmic_bytes_per_launch": bytes_alg,
+                     "note": "the on-demand form: its time is the atomics', at most %.3g of them per call, "
+                             "%.0f G/s here" % (atomics, atomics / dt / 1e9)},
+    }
+    pyr.destroy()
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +97,9 @@ def main() -> int:
                     help="also run the library's plain copy kernel on 1 GiB (3 launches) so that a counter run "
                          "sees a kernel of known HBM traffic")
     ap.add_argument("--print-source-sha", action="store_true", help="print the kernel-source hash and exit")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the gradient of the lookup (corr_sample_backward) instead: a step = one call on the "
+                         "workload's first coordinates; its own JSON line")
     ap.add_argument("--compare-modes", action="store_true",
                     help="additionally time the on-demand and full-volume reference modes (one lookup each)")
     args = ap.parse_args()
@@ -67,6 +120,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     cb.load_library()
+    if args.backward:
+        return bench_backward(args, cb, synth, torch, np)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = synth.config(args.config)

@@ -120,6 +120,29 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
                              float* out, void* stream);
 
 /*
+ * Gradient of the lookup with respect to the two feature maps (the paper names the backward pass as
+ * future work, Sec. "Conclusion"; the operation is the derivative of Eq. 1 with the coordinates held
+ * constant, as in RAFT, where they are detached):
+ *     d_fmap1, d_fmap2 = d/d(fmap1, fmap2) of  sum(d_out * corr_sample(fmap1, pyr(fmap2), coords)).
+ *   pyr       : built for the pair with CORR_REP_F32 (else CORR_ERR_MISSING_REP); its fmap1 copy and its
+ *               fmap2 levels are what the gradient is taken at.
+ *   coords    : device, fp32 [B, 2, H, W], as for corr_sample.
+ *   d_out     : device, fp32 [B, L*(2r+1)^2, H, W] (NCHW), read only.
+ *   d_fmap1, d_fmap2 : device, fp32 [B, D, H, W], fully overwritten.  The gradient of the pooled levels
+ *               is folded into d_fmap2 (adjoint of the 2x2 mean; a trailing odd row or column that the
+ *               pooling dropped receives level 0's share only).
+ *   workspace : device, at least corr_backward_workspace_bytes(B, H, W, D, L) bytes, 4-byte aligned,
+ *               caller-owned; contents on entry are ignored, contents on return are scratch.
+ * Enqueues kernels on `stream` and returns; allocates nothing.  fp32 throughout; d_fmap2 is accumulated
+ * with floating-point atomics, so two calls agree to rounding, not bit for bit.
+ */
+size_t corr_backward_workspace_bytes(int B, int H, int W, int D, int L);
+corr_status corr_sample_backward(const corr_pyramid* pyr, const float* coords, const float* d_out,
+                                 int B, int H, int W, int D, int L, int r,
+                                 float* d_fmap1, float* d_fmap2, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+/*
  * corr_sample for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and same kernels as
  * corr_sample (block mode, bf16x3, NCHW out), but the planning workspace of the lookup (bin

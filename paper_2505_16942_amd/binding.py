@@ -28,6 +28,7 @@ EXPORTS = [
     "corr_pyramid_build", "corr_pyramid_build_reps", "corr_pyramid_destroy", "corr_pyramid_bytes",
     "corr_sample", "corr_sample_mode", "corr_sample_layout", "corr_sample_static",
     "corr_full_volume_bytes", "corr_workspace_bytes", "corr_status_string",
+    "corr_backward_workspace_bytes", "corr_sample_backward",
 ]
 # measurement and test hooks (include/corr_bench.h)
 BENCH_EXPORTS = [
@@ -84,6 +85,10 @@ def load_library():
     lib.corr_sample_layout.restype = ci
     lib.corr_sample_static.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
     lib.corr_sample_static.restype = ci
+    lib.corr_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.corr_backward_workspace_bytes.restype = sz
+    lib.corr_sample_backward.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.corr_sample_backward.restype = ci
     lib.corr_full_volume_bytes.argtypes = [ci, ci, ci, ci]
     lib.corr_full_volume_bytes.restype = sz
     lib.corr_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci]
@@ -236,6 +241,44 @@ def corr_sample_static(fmap1, pyramid: Pyramid, coords: torch.Tensor, r: int = 4
     if st != CORR_OK:
         raise CorrError(st, "corr_sample_static")
     return out
+
+
+def corr_backward_workspace_bytes(B: int, H: int, W: int, D: int, L: int) -> int:
+    return int(load_library().corr_backward_workspace_bytes(B, H, W, D, L))
+
+
+def corr_sample_backward(pyramid: Pyramid, coords: torch.Tensor, d_out: torch.Tensor, r: int = 4,
+                         d_fmap1: torch.Tensor | None = None, d_fmap2: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None):
+    """Gradients of sum(d_out * lookup) with respect to fmap1 and fmap2: two fp32 tensors [B, D, H, W].
+    `workspace`: a device buffer of at least corr_backward_workspace_bytes() bytes (allocated here if None)."""
+    lib = load_library()
+    pc = _dev_f32(coords, "coords")
+    pg = _dev_f32(d_out, "d_out")
+    B, H, W, D, L = pyramid.B, pyramid.H, pyramid.W, pyramid.D, pyramid.L
+    K = 2 * r + 1
+    if tuple(coords.shape) != (B, 2, H, W):
+        raise ValueError("coords must be [B, 2, H, W] = %s" % ((B, 2, H, W),))
+    if tuple(d_out.shape) != (B, L * K * K, H, W):
+        raise ValueError("d_out must be [B, L*K*K, H, W] = %s" % ((B, L * K * K, H, W),))
+    need = corr_backward_workspace_bytes(B, H, W, D, L)
+    if workspace is None:
+        workspace = torch.empty(need // 4, dtype=torch.float32, device=coords.device)
+    if workspace.device != coords.device or not workspace.is_contiguous() or workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace must be a contiguous device buffer of at least %d bytes" % need)
+    outs = []
+    for t, name in ((d_fmap1, "d_fmap1"), (d_fmap2, "d_fmap2")):
+        if t is None:
+            t = torch.empty((B, D, H, W), dtype=torch.float32, device=coords.device)
+        elif tuple(t.shape) != (B, D, H, W):
+            raise ValueError("%s must be [B, D, H, W]" % name)
+        _dev_f32(t, name)
+        outs.append(t)
+    st = lib.corr_sample_backward(pyramid.handle, pc, pg, B, H, W, D, L, r, outs[0].data_ptr(), outs[1].data_ptr(),
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream())
+    if st != CORR_OK:
+        raise CorrError(st, "corr_sample_backward")
+    return outs[0], outs[1]
 
 
 def corr_last_block_stats(pyramid: Pyramid, r: int = 4) -> dict:

@@ -13,7 +13,7 @@ LIB = os.path.join(PKG, "libcorr_mi355x.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 # (source, object name, extra flags); block.hip is built once per lookup radius
 SOURCES = [("corr_api.hip", "corr_api.o", []), ("features.hip", "features.o", []), ("binning.hip", "binning.o", []),
-           ("ondemand.hip", "ondemand.o", []), ("fullvol.hip", "fullvol.o", [])]
+           ("ondemand.hip", "ondemand.o", []), ("fullvol.hip", "fullvol.o", []), ("backward.hip", "backward.o", [])]
 SOURCES += [("block.hip", "block_r%d.o" % r, ["-DCORR_BLOCK_R=%d" % r]) for r in (4, 3, 2, 1)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + INCLUDE, "-I" + CSRC,

@@ -467,6 +467,25 @@ corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32
     return hipStreamSynchronize(s) == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 
+size_t corr_backward_workspace_bytes(int B, int H, int W, int D, int L) {
+    if (check_dims(B, H, W, D, L) != CORR_OK) return 0;
+    return corr_backward_workspace_floats(B, H, W, D, L) * sizeof(float);
+}
+
+corr_status corr_sample_backward(const corr_pyramid* pyr, const float* coords, const float* d_out,
+                                 int B, int H, int W, int D, int L, int r,
+                                 float* d_fmap1, float* d_fmap2, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!d_fmap1 || !d_fmap2 || !workspace) return CORR_ERR_INVALID_ARG;
+    corr_status st = check_lookup_args(pyr, coords, d_out, B, H, W, D, L, r);
+    if (st != CORR_OK) return st;
+    if (!(pyr->built & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
+    if (workspace_bytes < corr_backward_workspace_floats(B, H, W, D, L) * sizeof(float)) return CORR_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0) return CORR_ERR_INVALID_ARG;
+    const hipError_t e = launch_backward(pyr, coords, d_out, r, d_fmap1, d_fmap2, static_cast<float*>(workspace),
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;
+}
+
 int corr_debug_set_level_split(int max_queries) {
     return g_split_levels_max.exchange(max_queries == -1 ? CORR_SPLIT_LEVELS_MAX_QUERIES : max_queries);
 }

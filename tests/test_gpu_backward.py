@@ -1,0 +1,119 @@
+"""GPU parity of the lookup's gradient (corr_sample_backward, through the C ABI) against the fp64 gradient
+oracle, element by element on the same seeded inputs.
+
+Bar: max|err| <= 1e-4 * max|gradient| per output (d_fmap1, d_fmap2).  The kernel works in fp32: an element of
+d_fmap1 is a sum of up to L * 100 terms, an element of d_fmap2 a sum over every query whose footprint
+covers the pixel (accumulated with atomics in arbitrary order, then a quarter per pooled level); both are
+relative errors of a few 1e-6 of the sum of magnitudes, inside the bound by an order of magnitude."""
+import numpy as np
+import pytest
+
+from oracle import corr_oracle as oracle
+from paper_2505_16942_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+CASES = [
+    # B, H, W, D, L, r, flow range
+    (1, 21, 35, 64, 3, 4, 7.0),       # odd level sizes: trailing rows and columns dropped by the pooling
+    (2, 16, 24, 32, 4, 4, 12.0),      # batch, D smaller than a wave
+    (1, 8, 8, 96, 4, 4, 3.0),         # level 3 is a single pixel; D not a multiple of 64
+    (1, 19, 27, 160, 2, 2, 30.0),     # r = 2, many windows outside
+    (1, 13, 17, 320, 4, 1, 5.0),      # r = 1, five channel slots per lane
+]
+
+
+def _binding():
+    from paper_2505_16942_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _check(got, want, what):
+    got = got.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got)), what + ": non-finite gradient (an element was not written?)"
+    m = float(np.abs(want).max())
+    err = float(np.abs(got - want).max())
+    print("%s: max|err| = %.3e, max|grad| = %.3f, bound = %.3e" % (what, err, m, TOL * m), flush=True)
+    assert err <= TOL * max(m, 1e-30), what
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_gradients_match_the_oracle(case):
+    B, H, W, D, L, r, fr = case
+    print("case", case, flush=True)
+    b = _binding()
+    dev = torch.device("cuda:0")
+    f1, f2, c = synth.small_case(300 + H, B, H, W, D, flow_range=fr)
+    c[0, :, 1, 2] = np.float32(-1e6)                   # out of range at every level: no gradient from it
+    c[B - 1, 0, 3, 1] = np.float32("nan")
+    K = 2 * r + 1
+    d_out = np.random.default_rng(H).standard_normal((B, L * K * K, H, W)).astype(np.float32)
+    want1, want2 = oracle.backward(f1, f2, c, d_out, L=L, r=r)
+    t1, t2, tc, tg = (torch.from_numpy(a).to(dev) for a in (f1, f2, c, d_out))
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_F32)
+    g1 = torch.full((B, D, H, W), float("nan"), device=dev)
+    g2 = torch.full((B, D, H, W), float("nan"), device=dev)
+    ws = torch.full((b.corr_backward_workspace_bytes(B, H, W, D, L) // 4,), float("nan"), device=dev)   # contents ignored
+    b.corr_sample_backward(pyr, tc, tg, r=r, d_fmap1=g1, d_fmap2=g2, workspace=ws)
+    torch.cuda.synchronize()
+    _check(g1, want1, "d_fmap1 %s" % (case,))
+    _check(g2, want2, "d_fmap2 %s" % (case,))
+    assert float(g1[0, :, 1, 2].abs().max()) == 0.0 and float(g1[B - 1, :, 3, 1].abs().max()) == 0.0
+    # a second call on the same workspace (now holding the first call's leftovers) gives the same result to rounding
+    h1, h2 = b.corr_sample_backward(pyr, tc, tg, r=r, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(h1, g1)                          # no atomics on this output: same bits
+    _check(h2, want2, "d_fmap2, second call %s" % (case,))
+    pyr.destroy()
+
+
+def test_backward_agrees_with_the_forward_kernel_by_the_adjoint_identity():
+    """<d_out, lookup(a, f2)> = <d_fmap1, a> with the library's own forward on the left: ties the two
+    directions of the library together at a size beyond the oracle's reach in a test (135 x 240, D = 256)."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    cfg = synth.config("1080p")
+    f1, f2 = synth.features(cfg)
+    c = synth.coords(cfg)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    gen = torch.Generator(device=dev); gen.manual_seed(5)
+    d_out = torch.randn((1, 324, 135, 240), device=dev, generator=gen)
+    a = torch.randn(t1.shape, device=dev, generator=gen)
+    pyr = b.corr_pyramid_build(t1, t2, L=4, reps=b.CORR_REP_F32 | b.CORR_REP_SPLIT)
+    g1, g2 = b.corr_sample_backward(pyr, tc, d_out)
+    pa = b.corr_pyramid_build(a, t2, L=4)               # the lookup of direction a against the same targets
+    lhs1 = float((d_out.double() * b.corr_sample(a, pa, tc).double()).sum())
+    rhs1 = float((g1.double() * a.double()).sum())
+    pb = b.corr_pyramid_build(t1, a, L=4)               # and of the pair (f1, a)
+    lhs2 = float((d_out.double() * b.corr_sample(t1, pb, tc).double()).sum())
+    rhs2 = float((g2.double() * a.double()).sum())
+    scale = float(d_out.abs().sum()) * 1e-7          # ~1e7 terms of size ~1: rounding of the two sides is far below this
+    print("adjoint identity: fmap1 %.6f vs %.6f, fmap2 %.6f vs %.6f (tolerance %.3f)" % (lhs1, rhs1, lhs2, rhs2, scale), flush=True)
+    assert abs(lhs1 - rhs1) <= scale and abs(lhs2 - rhs2) <= scale
+    for p in (pyr, pa, pb):
+        p.destroy()
+
+
+def test_backward_error_paths():
+    b = _binding()
+    dev = torch.device("cuda:0")
+    f = torch.zeros((1, 32, 8, 8), device=dev)
+    c = torch.zeros((1, 2, 8, 8), device=dev)
+    g = torch.zeros((1, 324, 8, 8), device=dev)
+    pyr = b.corr_pyramid_build(f, f, L=4)              # split representation only
+    with pytest.raises(b.CorrError) as e:
+        b.corr_sample_backward(pyr, c, g)
+    assert e.value.status == b.CORR_ERR_MISSING_REP
+    pyr.destroy()
+    pyr = b.corr_pyramid_build(f, f, L=4, reps=b.CORR_REP_F32)
+    small = torch.empty(16, device=dev)
+    with pytest.raises(ValueError):
+        b.corr_sample_backward(pyr, c, g, workspace=small)
+    lib = b.load_library()
+    st = lib.corr_sample_backward(pyr.handle, c.data_ptr(), g.data_ptr(), 1, 8, 8, 32, 4, 4, f.data_ptr(), f.data_ptr(),
+                                  small.data_ptr(), 64, None)
+    assert st == b.CORR_ERR_INVALID_ARG
+    pyr.destroy()
