@@ -25,7 +25,11 @@
 
 namespace {
 
-constexpr int SCAN_T = 1024;          // threads of a workgroup that scans
+
+constexpr int SCAN_T = 1024;          // cells per tile of the scan; threads of the one-workgroup path
+constexpr int COUNT_T = 1024;         // threads per workgroup of the count kernel (big workgroups are dispatched slowly:
+                                      // 1024-thread ones took 40 us to get going at 518 k queries); its last workgroup
+                                      // scans with SCAN_T / COUNT_T cells per thread
 constexpr int SMALL_MAX_Q = 2;        // queries per thread of the one-workgroup path
 
 struct BinArgs {
@@ -37,7 +41,7 @@ struct BinArgs {
     BinWs ws;
 };
 
-// bin of query (b, p), or -1 when it is out of range at every level (then its output column is zeroed here)
+// bin of query (b, p), or -1 when it is out of range at every level (the scatter kernel then writes its zeros)
 __device__ __forceinline__ int query_bin(const BinArgs& a, int b, int p) {
     const float cx = a.coords[((size_t)b * 2 + 0) * a.HW + p];
     const float cy = a.coords[((size_t)b * 2 + 1) * a.HW + p];
@@ -50,12 +54,17 @@ __device__ __forceinline__ int query_bin(const BinArgs& a, int b, int p) {
         if (u >= 0 && u < a.g.nbx && v >= 0 && v < a.g.nby)
             bin = corr_cell_id(a.g, b, u, v) * CORR_SUB + ((p / a.W) & (CORR_SUB - 1));
     }
-    if (bin < 0) {
-        const int K = 2 * a.r + 1;
-        float* o = a.out + (size_t)b * a.L * K * K * a.HW + (size_t)p * a.pix_stride;
-        for (int t = 0; t < a.L * K * K; ++t) o[(size_t)t * a.tap_stride] = 0.0f;
-    }
     return bin;
+}
+
+// A query without a bin never reaches the block kernel: all its taps are zero, written here.  Lane = query:
+// null queries cluster (image borders, regions whose targets lie outside), so neighbouring lanes write
+// neighbouring pixels of the same tap plane and their stores merge into one request; a wave writing one query
+// at a time with the taps across its lanes was four times slower (every lane a request of its own).
+__device__ __forceinline__ void zero_taps(const BinArgs& a, int b, int p) {
+    const int K = 2 * a.r + 1, taps = a.L * K * K;
+    float* o = a.out + (size_t)b * taps * a.HW + (size_t)p * a.pix_stride;
+    for (int t = 0; t < taps; ++t) o[(size_t)t * a.tap_stride] = 0.0f;
 }
 
 // Neighbouring pixels mostly fall in the same bin: one atomic per run of equal bins among
@@ -85,83 +94,130 @@ __device__ __forceinline__ int take_rank(int* bin_count, int bin) {
     return take_rank_finish(take_rank_issue(bin_count, bin));
 }
 
-// One workgroup of SCAN_T threads: exclusive scan of the bin counts (query offsets) and of the
-// per-cell item counts, one cell per thread and tile; writes the item list in cell order and
-// clears the counts for the next lookup.  Counts are read with device-scope atomic loads: they
-// were produced by atomics of other workgroups, possibly on other XCDs.
+// One workgroup of T threads: exclusive scan of the bin counts (query offsets) and of the per-cell item
+// counts, CPT consecutive cells per thread and tile of T * CPT cells; writes the item list in cell order and
+// clears the counts for the next lookup.  The counts were produced by device-scope atomics of other
+// workgroups, possibly on other XCDs: a caller that runs in the same kernel as those atomics puts an
+// acquire fence in front (this XCD's L2 may hold stale copies of the lines).
+template <int T, int CPT>
 __device__ void scan_cells(const BinWs& ws) {
-    __shared__ int s_wc[SCAN_T / 64], s_wi[SCAN_T / 64];
+    static_assert(CORR_SUB == 8, "a cell's counters are two int4");
+    __shared__ int s_wc[T / 64], s_wi[T / 64], s_tot[2];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     int carry_c = 0, carry_i = 0;
-    const int ntiles = (ws.ncells + SCAN_T - 1) / SCAN_T;
+    const int ntiles = (ws.ncells + T * CPT - 1) / (T * CPT);
     for (int tile = 0; tile < ntiles; ++tile) {
-        const int cell = tile * SCAN_T + t;
-        int c[CORR_SUB];
-        int csum = 0;
+        const int cell0 = (tile * T + t) * CPT;
+        // a cell's counters are 32 contiguous bytes: two 16-byte loads per cell, all of a thread's in flight at once
+        int4 lo[CPT], hi[CPT];
 #pragma unroll
-        for (int k = 0; k < CORR_SUB; ++k) {
-            c[k] = cell < ws.ncells ? __hip_atomic_load(&ws.bin_count[cell * CORR_SUB + k], __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT) : 0;
-            csum += c[k];
+        for (int j = 0; j < CPT; ++j) {
+            lo[j] = make_int4(0, 0, 0, 0); hi[j] = lo[j];
+            if (cell0 + j < ws.ncells) {
+                const int4* pc = reinterpret_cast<const int4*>(ws.bin_count + (size_t)(cell0 + j) * CORR_SUB);
+                lo[j] = pc[0]; hi[j] = pc[1];
+            }
         }
-        const int isum = (csum + CORR_GROUP - 1) / CORR_GROUP;
-        int ci = csum, ii = isum;                   // inclusive scan within the wave
+        int csum[CPT], isum[CPT], tc = 0, ti = 0;
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            csum[j] = lo[j].x + lo[j].y + lo[j].z + lo[j].w + hi[j].x + hi[j].y + hi[j].z + hi[j].w;
+            isum[j] = (csum[j] + CORR_GROUP - 1) / CORR_GROUP;
+            tc += csum[j]; ti += isum[j];
+        }
+        int ci = tc, ii = ti;                       // inclusive scan within the wave
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const int vc = __shfl_up(ci, d, 64), vi = __shfl_up(ii, d, 64);
             if (lane >= d) { ci += vc; ii += vi; }
         }
-        __syncthreads();                            // previous tile's s_wc/s_wi fully consumed
+        __syncthreads();                            // previous tile's shared values fully consumed
         if (lane == 63) { s_wc[wave] = ci; s_wi[wave] = ii; }
         __syncthreads();
-        int wc = 0, wi = 0, tot_c = 0, tot_i = 0;
+        // the waves' totals are scanned by the first wave (a shuffle scan over T / 64 lanes): every thread
+        // then needs two values only, which keeps this function's registers, and with them the registers of
+        // the kernel that carries it, low
+        if (wave == 0) {
+            int vc = lane < T / 64 ? s_wc[lane] : 0, vi = lane < T / 64 ? s_wi[lane] : 0;
+            const int oc = vc, oi = vi;
 #pragma unroll
-        for (int w = 0; w < SCAN_T / 64; ++w) {
-            const int vc = s_wc[w], vi = s_wi[w];
-            if (w < wave) { wc += vc; wi += vi; }
-            tot_c += vc; tot_i += vi;
+            for (int d = 1; d < T / 64; d <<= 1) {
+                const int uc = __shfl_up(vc, d, 64), ui = __shfl_up(vi, d, 64);
+                if (lane >= d) { vc += uc; vi += ui; }
+            }
+            if (lane < T / 64) { s_wc[lane] = vc - oc; s_wi[lane] = vi - oi; }       // exclusive prefix per wave
+            if (lane == T / 64 - 1) { s_tot[0] = vc; s_tot[1] = vi; }
         }
-        int coff = carry_c + wc + ci - csum, ioff = carry_i + wi + ii - isum;
+        __syncthreads();
+        const int wc = s_wc[wave], wi = s_wi[wave], tot_c = s_tot[0], tot_i = s_tot[1];
+        int coff = carry_c + wc + ci - tc, ioff = carry_i + wi + ii - ti;
         carry_c += tot_c; carry_i += tot_i;
-        if (cell < ws.ncells) {
-            for (int s = 0; s < csum; s += CORR_GROUP)
-                ws.items[ioff++] = make_int4(cell, coff + s, min(CORR_GROUP, csum - s), 0);
 #pragma unroll
-            for (int k = 0; k < CORR_SUB; ++k) {
-                ws.bin_off[cell * CORR_SUB + k] = coff;
-                ws.bin_count[cell * CORR_SUB + k] = 0;          // ready for the next lookup
-                coff += c[k];
+        for (int j = 0; j < CPT; ++j) {
+            const int cell = cell0 + j;
+            if (cell < ws.ncells) {
+                for (int s = 0; s < csum[j]; s += CORR_GROUP)
+                    ws.items[ioff++] = make_int4(cell, coff + s, min(CORR_GROUP, csum[j] - s), 0);
+                // a cell's eight offsets and eight cleared counters: 16-byte stores (one store instruction per
+                // 4-byte entry would be one memory request per lane and entry)
+                const int o1 = coff + lo[j].x, o2 = o1 + lo[j].y, o3 = o2 + lo[j].z, o4 = o3 + lo[j].w;
+                const int o5 = o4 + hi[j].x, o6 = o5 + hi[j].y, o7 = o6 + hi[j].z;
+                int4* po = reinterpret_cast<int4*>(ws.bin_off + (size_t)cell * CORR_SUB);
+                int4* pc = reinterpret_cast<int4*>(ws.bin_count + (size_t)cell * CORR_SUB);
+                po[0] = make_int4(coff, o1, o2, o3);
+                po[1] = make_int4(o4, o5, o6, o7);
+                pc[0] = make_int4(0, 0, 0, 0);                   // ready for the next lookup
+                pc[1] = make_int4(0, 0, 0, 0);
+                coff += csum[j];
             }
         }
     }
     if (t == 0) { ws.n_items[0] = carry_i; ws.n_items[1] = carry_c; ws.n_items[2] = 0; }
+    if (t < CORR_NTICKETS) ws.n_items[4 + t * CORR_TICKET_STRIDE] = 0;              // tickets ready for the next lookup
 }
 
-__global__ __launch_bounds__(SCAN_T) void bin_count_kernel(BinArgs a) {
+__global__ __launch_bounds__(COUNT_T) void bin_count_kernel(BinArgs a) {
     __shared__ int s_last;
     const int q = blockIdx.x * blockDim.x + threadIdx.x;   // b*HW + pixel
     const int BN = a.B * a.HW;
     const bool real = q < BN;                 // lanes past the end stay for the shuffles
     int bin = -1;
-    if (real) { const int b = q / a.HW; bin = query_bin(a, b, q - b * a.HW); }
+    const int b = real ? q / a.HW : 0, p = real ? q - b * a.HW : 0;
+    if (real) bin = query_bin(a, b, p);
     const int rank = take_rank(a.ws.bin_count, bin);
     if (real) { a.ws.q_bin[q] = bin; a.ws.q_rank[q] = rank; }
     // The workgroup that arrives last scans.  Every thread has its atomic's result back before the
-    // barrier, so the workgroup's additions are done when thread 0 takes the ticket; the scan reads
-    // the counters with device-scope loads.
+    // barrier: the workgroup's additions have been performed at the device's coherence point when thread 0
+    // takes the ticket, and the scan reads the counters there too (device-scope atomic loads).  Counters and
+    // ticket are only ever touched by device-scope atomics, so the ticket needs no fence of its own; a
+    // release/acquire here would write back and invalidate the XCD's whole L2 once per workgroup, which is
+    // what this kernel's time used to be (0.14 ms of it at 518 k queries).
     __syncthreads();
-    if (threadIdx.x == 0)
-        s_last = __hip_atomic_fetch_add(&a.ws.n_items[2], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1;
+    if (threadIdx.x == 0) {
+        // Two-stage sign-off: atomics on one address are served one after the other (50..80 ns each here), so
+        // the workgroups spread over CORR_NTICKETS sub-tickets and only the last one on each takes the top one.
+        const int sub = blockIdx.x % CORR_NTICKETS;
+        const int on_sub = ((int)gridDim.x - sub + CORR_NTICKETS - 1) / CORR_NTICKETS;
+        const int subs = min((int)gridDim.x, CORR_NTICKETS);
+        bool last = __hip_atomic_fetch_add(&a.ws.n_items[4 + sub * CORR_TICKET_STRIDE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == on_sub - 1;
+        if (last) last = __hip_atomic_fetch_add(&a.ws.n_items[2], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == subs - 1;
+        s_last = last;
+    }
     __syncthreads();
-    if (s_last) scan_cells(a.ws);
+    if (s_last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");          // once, in one workgroup: drop stale lines, then read normally
+        scan_cells<COUNT_T, SCAN_T / COUNT_T>(a.ws);
+        __syncthreads();
+    }
 }
 
 __global__ __launch_bounds__(256) void bin_scatter_kernel(BinArgs a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= a.B * a.HW) return;
     const int bin = a.ws.q_bin[i];
+    const int b = i / a.HW, p = i - b * a.HW;
+    if (bin < 0) zero_taps(a, b, p);
     if (bin >= 0) {
-        const int b = i / a.HW, p = i - b * a.HW;
         const int pos = a.ws.bin_off[bin] + a.ws.q_rank[i];
         a.ws.perm[pos] = i;
         a.ws.sorted_c[pos] = make_float2(a.coords[((size_t)b * 2 + 0) * a.HW + p], a.coords[((size_t)b * 2 + 1) * a.HW + p]);
@@ -177,7 +233,9 @@ __global__ __launch_bounds__(SCAN_T) void bin_small_kernel(BinArgs a) {
     for (int k = 0; k < SMALL_MAX_Q; ++k) {
         const int q = k * SCAN_T + threadIdx.x;
         bin[k] = -1;
-        if (q < BN) { const int b = q / a.HW; bin[k] = query_bin(a, b, q - b * a.HW); }
+        const int b = q < BN ? q / a.HW : 0, p = q < BN ? q - b * a.HW : 0;
+        if (q < BN) bin[k] = query_bin(a, b, p);
+        if (q < BN && bin[k] < 0) zero_taps(a, b, p);
     }
     // all of a thread's atomics are in flight before the first result is used
 #pragma unroll
@@ -188,7 +246,7 @@ __global__ __launch_bounds__(SCAN_T) void bin_small_kernel(BinArgs a) {
 #pragma unroll
     for (int k = 0; k < SMALL_MAX_Q; ++k) rank[k] = (k * SCAN_T < BN) ? take_rank_finish(ticket[k]) : 0;
     __syncthreads();                  // every atomic of this workgroup has returned
-    scan_cells(a.ws);
+    scan_cells<SCAN_T, 1>(a.ws);
     __syncthreads();                  // the offsets were written by threads of this workgroup
 #pragma unroll
     for (int k = 0; k < SMALL_MAX_Q; ++k) {
@@ -284,7 +342,7 @@ hipError_t launch_binning(const corr_pyramid* p, const BinWs& ws, const LookupAr
         hipLaunchKernelGGL(bin_small_kernel, dim3(1), dim3(SCAN_T), 0, s, a);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(bin_count_kernel, dim3((BN + SCAN_T - 1) / SCAN_T), dim3(SCAN_T), 0, s, a);
+    hipLaunchKernelGGL(bin_count_kernel, dim3((BN + COUNT_T - 1) / COUNT_T), dim3(COUNT_T), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(bin_scatter_kernel, dim3((BN + 255) / 256), dim3(256), 0, s, a);

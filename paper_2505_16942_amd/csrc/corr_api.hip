@@ -372,7 +372,7 @@ corr_status corr_sample_static(const float* fmap1, const corr_pyramid* pyr, cons
     // the array keeps the last call's contents, laid out for that call's sizes: the bin counters and
     // the item / ticket counters must start at zero (fill kernels, so the call can be graph-captured)
     hipError_t e = launch_fill_i32(ws.bin_count, 0, (size_t)ws.nbins, s);
-    if (e == hipSuccess) e = launch_fill_i32(ws.n_items, 0, 4, s);
+    if (e == hipSuccess) e = launch_fill_i32(ws.n_items, 0, CORR_NCOUNTERS, s);
     LookupArgs q;
     q.coords = coords; q.out = out; q.r = r; q.nhwc = 0; q.prec = (int)CORR_PREC_BF16X3;
     q.split_levels_max = g_split_levels_max.load();

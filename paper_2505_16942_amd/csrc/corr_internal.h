@@ -29,6 +29,9 @@
 #endif
 #define CORR_COORD_LIMIT 1048576.0f
 #define CORR_NSTATS 24
+#define CORR_NTICKETS 16       // the count kernel's workgroups sign off on one of these, so that no counter sees them all
+#define CORR_TICKET_STRIDE 32  // ints between sub-tickets: one cache line each
+#define CORR_NCOUNTERS (4 + CORR_NTICKETS * CORR_TICKET_STRIDE)
 
 // Target-cell grid.  A query belongs to the cell (floor(cx) >> LOG_CX,
 // floor(cy) >> LOG_CY).  Because floor(c / 2^l) == floor(c) >> l, all queries of
@@ -79,7 +82,7 @@ struct BinWs {
     int* perm;                     // [B*H*W] queries sorted by bin
     float2* sorted_c;              // [B*H*W] their coordinates (x, y), in the same order
     int4* items;                   // [max_items] {cell id, first perm index, n queries, 0}
-    int* n_items;                  // [4]: items, binned queries, count-kernel tickets, 0
+    int* n_items;                  // [CORR_NCOUNTERS]: items, binned queries, top ticket, 0, then CORR_NTICKETS sub-tickets CORR_TICKET_STRIDE ints apart
     long long* stats;              // [CORR_NSTATS]: 8+4*l+{0,1,2,3} per level
     int ncells, nbins, max_items;
 };
@@ -141,7 +144,7 @@ static inline WsLayout corr_ws_layout(int BN, int ncells) {
     w.perm = o; o = up(o + (size_t)BN * 4);
     w.sorted_c = o; o = up(o + (size_t)BN * 8);
     w.items = o; o = up(o + (size_t)corr_max_items(BN, ncells) * 16);
-    w.n_items = o; o = up(o + 16);
+    w.n_items = o; o = up(o + CORR_NCOUNTERS * 4);
     w.stats = o; o = up(o + CORR_NSTATS * 8);
     w.total = o;
     return w;
