@@ -34,14 +34,12 @@ constexpr int SMALL_MAX_Q = 2;        // queries per thread of the one-workgroup
 
 struct BinArgs {
     const float* coords;   // [B][2][H*W]
-    float* out;            // [B][L*K*K][H*W]
     int B, HW, W, L, r;           // r: radius of this lookup (the grid is laid out for the largest)
-    int tap_stride, pix_stride;   // layout of out
     CellGrid g;
     BinWs ws;
 };
 
-// bin of query (b, p), or -1 when it is out of range at every level (the scatter kernel then writes its zeros)
+// bin of query (b, p), or -1 when it is out of range at every level (the block kernel's spare workgroups then write its zeros)
 __device__ __forceinline__ int query_bin(const BinArgs& a, int b, int p) {
     const float cx = a.coords[((size_t)b * 2 + 0) * a.HW + p];
     const float cy = a.coords[((size_t)b * 2 + 1) * a.HW + p];
@@ -55,16 +53,6 @@ __device__ __forceinline__ int query_bin(const BinArgs& a, int b, int p) {
             bin = corr_cell_id(a.g, b, u, v) * CORR_SUB + ((p / a.W) & (CORR_SUB - 1));
     }
     return bin;
-}
-
-// A query without a bin never reaches the block kernel: all its taps are zero, written here.  Lane = query:
-// null queries cluster (image borders, regions whose targets lie outside), so neighbouring lanes write
-// neighbouring pixels of the same tap plane and their stores merge into one request; a wave writing one query
-// at a time with the taps across its lanes was four times slower (every lane a request of its own).
-__device__ __forceinline__ void zero_taps(const BinArgs& a, int b, int p) {
-    const int K = 2 * a.r + 1, taps = a.L * K * K;
-    float* o = a.out + (size_t)b * taps * a.HW + (size_t)p * a.pix_stride;
-    for (int t = 0; t < taps; ++t) o[(size_t)t * a.tap_stride] = 0.0f;
 }
 
 // Neighbouring pixels mostly fall in the same bin: one atomic per run of equal bins among
@@ -215,9 +203,8 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(BinArgs a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= a.B * a.HW) return;
     const int bin = a.ws.q_bin[i];
-    const int b = i / a.HW, p = i - b * a.HW;
-    if (bin < 0) zero_taps(a, b, p);
     if (bin >= 0) {
+        const int b = i / a.HW, p = i - b * a.HW;
         const int pos = a.ws.bin_off[bin] + a.ws.q_rank[i];
         a.ws.perm[pos] = i;
         a.ws.sorted_c[pos] = make_float2(a.coords[((size_t)b * 2 + 0) * a.HW + p], a.coords[((size_t)b * 2 + 1) * a.HW + p]);
@@ -234,8 +221,7 @@ __global__ __launch_bounds__(SCAN_T) void bin_small_kernel(BinArgs a) {
         const int q = k * SCAN_T + threadIdx.x;
         bin[k] = -1;
         const int b = q < BN ? q / a.HW : 0, p = q < BN ? q - b * a.HW : 0;
-        if (q < BN) bin[k] = query_bin(a, b, p);
-        if (q < BN && bin[k] < 0) zero_taps(a, b, p);
+        if (q < BN) { bin[k] = query_bin(a, b, p); a.ws.q_bin[q] = bin[k]; }     // the block kernel looks for the queries without a bin
     }
     // all of a thread's atomics are in flight before the first result is used
 #pragma unroll
@@ -335,8 +321,7 @@ hipError_t launch_bin_stats(const corr_pyramid* p, const BinWs& ws, int r, hipSt
 hipError_t launch_binning(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s) {
     const int HW = p->H * p->W, BN = p->B * HW;
     BinArgs a;
-    a.coords = q.coords; a.out = q.out; a.B = p->B; a.HW = HW; a.W = p->W; a.L = p->L; a.r = q.r; a.g = p->grid;
-    a.tap_stride = corr_tap_stride(p, q); a.pix_stride = corr_pix_stride(p, q);
+    a.coords = q.coords; a.B = p->B; a.HW = HW; a.W = p->W; a.L = p->L; a.r = q.r; a.g = p->grid;
     a.ws = ws;
     if (BN <= SCAN_T * SMALL_MAX_Q) {
         hipLaunchKernelGGL(bin_small_kernel, dim3(1), dim3(SCAN_T), 0, s, a);

@@ -64,6 +64,7 @@ struct BlockArgs {
     const float2* sorted_c;              // their coordinates
     const int4* items;
     const int* n_items;
+    const int* q_bin;                    // [B*HW] bin of every query, -1: no bin (out of range at every level)
     float* out;
     int B, HW, NC, L;
     int tap_stride, pix_stride;          // layout of out
@@ -531,18 +532,39 @@ __device__ __forceinline__ void run_levels(const BlockArgs& a, const ItemCtx& c,
     if (a.L > 3) level_pass<3, THREE, BIGD, NHWC, TWO>(a, c, smem, qhi, qlo, p3, p3);
 }
 
-// What every workgroup sets up first: its item (XCD-aware choice; the grid covers the largest possible item
-// count and the tail exits), the thread's indices, the LDS addresses, the buffer resource of the pyramid.
-// Returns false when there is no item for this workgroup.
+// Part `part` of `parts` of the query range: zeros for every query without a bin.  Lane = query: null
+// queries cluster (image borders, regions whose targets lie outside), so neighbouring lanes write neighbouring
+// pixels of one tap plane and their stores merge.
+__device__ __forceinline__ void zero_null_queries(const BlockArgs& a, int part, int parts) {
+    const int BN = a.B * a.HW;
+    const int per = (BN + parts - 1) / parts;
+    const int q0 = part * per, q1 = min(BN, q0 + per);
+    const int taps = a.L * KK;
+    for (int i = q0; i < q1; i += NT) {               // the same trip count for every thread
+        const int q = i + (int)threadIdx.x;
+        if (q < q1 && a.q_bin[q] < 0) {
+            const int b = q / a.HW, p = q - b * a.HW;
+            float* o = a.out + (size_t)b * taps * a.HW + (size_t)p * a.pix_stride;
+            for (int t = 0; t < taps; ++t) o[(size_t)t * a.tap_stride] = 0.0f;
+        }
+    }
+}
+
+// Which item this workgroup takes, or -1 - s when there is none and it is workgroup s of those past the item
+// list.  XCD-aware choice (the grid covers the largest possible item count); SPREAD: consecutive items on
+// different XCDs instead (workgroup w runs on XCD w % 8): with few items the runs of the XCD-aware choice would
+// put them all on one or two XCDs and leave the other compute units idle.
 template <bool SPREAD = false>
-__device__ __forceinline__ bool init_item(const BlockArgs& a, unsigned char* smem, ItemCtx& c, int4& item) {
+__device__ __forceinline__ int choose_item(const BlockArgs& a) {
+    const int n_items = *a.n_items;
+    const int k = SPREAD ? (int)blockIdx.x : corr_item_of_workgroup(blockIdx.x);
+    return k < n_items ? k : -1 - (k - n_items);
+}
+// What a workgroup with an item sets up first: the item's record, the thread's indices, the LDS addresses, the
+// buffer resource of the pyramid.
+__device__ __forceinline__ void init_item(const BlockArgs& a, unsigned char* smem, int k, ItemCtx& c, int4& item) {
     int* q_pix = reinterpret_cast<int*>(smem + LDS_DATA);
     float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP);
-    const int n_items = *a.n_items;
-    // SPREAD: consecutive items on different XCDs (workgroup w runs on XCD w % 8).  With few items the runs
-    // of the XCD-aware choice would put them all on one or two XCDs and leave the other compute units idle.
-    const int k = SPREAD ? (int)blockIdx.x : corr_item_of_workgroup(blockIdx.x);
-    if (k >= n_items) return false;
     item = a.items[k];
     c.item = k;
     c.tid = threadIdx.x; c.lane = c.tid & 63;
@@ -559,7 +581,6 @@ __device__ __forceinline__ bool init_item(const BlockArgs& a, unsigned char* sme
     c.rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)base);
     c.rsrc[1] = __builtin_amdgcn_readfirstlane((int)((base >> 32) & 0xffffu));
     c.rsrc[2] = __builtin_amdgcn_readfirstlane((int)a.f2_plane_bytes); c.rsrc[3] = 0x00020000;
-    return true;
 }
 // the item's query records (pixel, x, y) from the sorted list into LDS
 __device__ __forceinline__ void load_records(const BlockArgs& a, const ItemCtx& c, const int4& item) {
@@ -580,9 +601,17 @@ __device__ __forceinline__ void load_records(const BlockArgs& a, const ItemCtx& 
 template <bool THREE, bool BIGD, bool NHWC>
 __global__ __launch_bounds__(NT, 1) void block_kernel(BlockArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    const int k = choose_item(a);
+    if (k < 0) {
+        // No item: this workgroup writes zeros instead.  Queries without a bin never reach an item (all their taps
+        // are zero); the workgroups past the item list share the query range and zero the ones they find.  They
+        // are dispatched last, so the fill runs beside the last items instead of before the first.
+        zero_null_queries(a, -1 - k, (int)gridDim.x - *a.n_items);
+        return;
+    }
     ItemCtx c;
     int4 item;
-    if (!init_item(a, smem, c, item)) return;
+    init_item(a, smem, k, c, item);
 
     TRACE(0);
     // level 0's first unit starts to move before anything else
@@ -635,9 +664,14 @@ __device__ __forceinline__ void level_range(const BlockArgs& a, const ItemCtx& c
 template <bool THREE, bool BIGD, bool NHWC>
 __global__ __launch_bounds__(NT, 1) void block_level_kernel(BlockArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    const int k = choose_item<true>(a);
+    if (k < 0) {
+        if (blockIdx.y == 0) zero_null_queries(a, -1 - k, (int)gridDim.x - *a.n_items);      // as in block_kernel
+        return;
+    }
     ItemCtx c;
     int4 item;
-    if (!init_item<true>(a, smem, c, item)) return;
+    init_item(a, smem, k, c, item);
     const int n_items = *a.n_items;
     const int ways = a.force_ways ? a.force_ways : CORR_MAX_L * n_items <= CORR_NUM_CU ? CORR_MAX_L : 2 * n_items <= 3 * CORR_NUM_CU ? 2 : 1;
     const int y = blockIdx.y;                      // uniform, like everything above
@@ -670,7 +704,7 @@ hipError_t launch_items(const corr_pyramid* p, const BinWs& ws, const LookupArgs
     if (attr_levels != hipSuccess) return attr_levels;
     BlockArgs a;
     a.f1s = p->f1_split; a.f2s = p->f2_split; a.perm = ws.perm; a.sorted_c = ws.sorted_c; a.items = ws.items;
-    a.n_items = ws.n_items; a.out = q.out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L;
+    a.n_items = ws.n_items; a.q_bin = ws.q_bin; a.out = q.out; a.B = p->B; a.HW = p->H * p->W; a.NC = p->D / CORR_CHUNK; a.L = p->L;
     a.tap_stride = corr_tap_stride(p, q); a.pix_stride = corr_pix_stride(p, q);
     a.g = p->grid;
     for (int l = 0; l < CORR_MAX_L; ++l) { a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l]; a.pix_base[l] = p->f2_pix_base[l]; }
