@@ -27,9 +27,9 @@ namespace {
 
 
 constexpr int SCAN_T = 1024;          // cells per tile of the scan; threads of the one-workgroup path
-constexpr int COUNT_T = 1024;         // threads per workgroup of the count kernel (big workgroups are dispatched slowly:
-                                      // 1024-thread ones took 40 us to get going at 518 k queries); its last workgroup
-                                      // scans with SCAN_T / COUNT_T cells per thread
+constexpr int COUNT_T = 1024;         // threads per workgroup of the count kernel
+constexpr int SCAN_CPT = 1;           // cells per thread and tile when its last workgroup scans (2 was no faster, 4 costs
+                                      // the kernel its two workgroups per CU)
 constexpr int SMALL_MAX_Q = 2;        // queries per thread of the one-workgroup path
 
 struct BinArgs {
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(COUNT_T) void bin_count_kernel(BinArgs a) {
     __syncthreads();
     if (s_last) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");          // once, in one workgroup: drop stale lines, then read normally
-        scan_cells<COUNT_T, SCAN_T / COUNT_T>(a.ws);
+        scan_cells<COUNT_T, SCAN_CPT>(a.ws);
         __syncthreads();
     }
 }
