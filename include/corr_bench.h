@@ -86,6 +86,16 @@ corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32
  */
 int corr_debug_set_level_split(int max_queries);
 /*
+ * Test and measurement hook (process-wide): which kernel corr_sample_backward runs.  CORR_BACKWARD_ITEMS (the
+ * default): the forward pass's work items, both gradients as fp32 matrix-core contractions over an item's
+ * windows.  CORR_BACKWARD_QUERIES: one wave per query on the vector ALU with a float atomic per footprint
+ * point and channel (the earlier form; kept as a cross-check and as the slower side of the comparison).
+ * Both give the same gradients up to fp32 summation order.  Returns the previous setting.
+ */
+#define CORR_BACKWARD_ITEMS 0
+#define CORR_BACKWARD_QUERIES 1
+int corr_debug_set_backward_form(int form);
+/*
  * Test hook (host only, no GPU work): the block kernel's launch grid for a workspace that can hold
  * `max_items` work items, and which item each workgroup takes: map[w] for w < *grid.  Pass map = NULL
  * to get the grid size alone; CORR_ERR_INVALID_ARG if map_cap < *grid.

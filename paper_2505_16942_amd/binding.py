@@ -35,6 +35,7 @@ BENCH_EXPORTS = [
     "corr_last_block_stats", "corr_profile_enable", "corr_profile_read", "corr_bin_geometry", "corr_copy_f32",
     "corr_debug_read_plan", "corr_debug_cell_coords", "corr_debug_read_level", "corr_debug_item_map",
     "corr_debug_set_level_split",
+    "corr_debug_set_backward_form",
 ]
 
 
@@ -112,6 +113,8 @@ def load_library():
     lib.corr_debug_item_map.restype = ci
     lib.corr_debug_set_level_split.argtypes = [ci]
     lib.corr_debug_set_level_split.restype = ci
+    lib.corr_debug_set_backward_form.argtypes = [ci]
+    lib.corr_debug_set_backward_form.restype = ci
     lib.corr_debug_read_level.argtypes = [vp, cu, ci, ctypes.POINTER(ctypes.c_float), vp]
     lib.corr_debug_read_level.restype = ci
     lib.corr_status_string.argtypes = [ci]
@@ -331,6 +334,15 @@ def corr_debug_read_plan(pyramid: Pyramid):
     if st != CORR_OK:
         raise CorrError(st, "corr_debug_read_plan")
     return items[:counts[0]].copy(), perm[:counts[1]].copy()
+
+
+CORR_BACKWARD_ITEMS, CORR_BACKWARD_QUERIES = 0, 1
+
+
+def corr_debug_set_backward_form(form: int) -> int:
+    """Which kernel corr_sample_backward runs (CORR_BACKWARD_ITEMS, the default, or CORR_BACKWARD_QUERIES);
+    returns the previous setting."""
+    return int(load_library().corr_debug_set_backward_form(int(form)))
 
 
 def corr_debug_set_level_split(max_queries: int) -> int:

@@ -102,6 +102,241 @@ __global__ __launch_bounds__(64 * BQ) void bwd_query_kernel(BwdArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The item form: the same work items as the forward block kernel (a target cell and up to 128 of its queries,
+// one fixed window of level-l points per level), and both gradients as dense contractions on the matrix cores.
+// For one item and level, with G[point][query] the footprint weights of every query scattered over the window
+// (zero outside the query's footprint) and 1/sqrt(D) folded in:
+//     d f1[query][:]       += sum over points  G[point][query] * f2_l[point][:]       (M = queries, K = points)
+//     d f2_l[point][:]     += sum over queries G[point][query] * f1[query][:]         (M = points,  K = queries)
+// fp32 throughout: v_mfma_f32_16x16x4_f32 takes one fp32 element of A and of B per lane, so G (in LDS, one
+// column per query) and the channels-last fp32 feature rows feed it without any transposition.  G is built
+// CH points at a time from the tap gradients (a footprint point collects up to four taps); d f1 stays in
+// accumulators over all levels and is stored once (a query belongs to one item); the window's d f2_l rows go
+// out through float atomics once per item and pass, instead of once per query and footprint point.
+// Eight waves, two per SIMD: a wave owns 32 channels of a 256-channel group; lane = (K index lane/16, M or N
+// index lane%16).  Feature rows come through buffer resources: an offset past the end reads zero and an atomic
+// there is dropped, so rows outside the level and empty query slots need no branch inside the loops.
+constexpr int NTI = 512;
+constexpr int GST = CORR_GROUP + 4;         // floats between G rows (bank shift 4 per row: a 16-row x 4-query read is conflict-free)
+constexpr int CH = 144;                     // window points per pass: level 2's window in one pass, level 0's in three
+constexpr int MTC = CH / 16;
+constexpr int NTW = 2;                      // 16-channel tiles per wave
+constexpr int TAB_PAD = 16;                 // the operand loads run three k-steps ahead: the tables end in invalid entries
+constexpr int ITEM_LDS = CH * GST * 4 + (CH + TAB_PAD) * 4 + (CORR_GROUP + TAB_PAD) * 4 + CORR_GROUP * 8;
+constexpr unsigned BAD_OFF = 0x80000000u;   // beyond every buffer here (each is below 2 GiB)
+
+struct BwdItemArgs {
+    const float* f1;
+    const float* f2[CORR_MAX_L];
+    float* d_f1;                            // zero on entry (queries without an item keep the zero)
+    float* d_f2[CORR_MAX_L];                // zero on entry, accumulated
+    const float* d_out;
+    const int* perm;
+    const float2* sorted_c;
+    const int4* items;
+    const int* n_items;
+    int B, HW, D, L, r;
+    int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
+    CellGrid g;
+    float scale;
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4 mma4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const float* base, size_t floats) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)(unsigned)(floats * 4), 0x00020000);
+}
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, unsigned off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+
+// NMT: 16-query tiles the item fills (its query count rounded up to 32 or more: 2, 4, 6 or 8)
+template <int NMT>
+__device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item) {
+    float* G = reinterpret_cast<float*>(smem);                   // [CH][GST]
+    int* rowpix = reinterpret_cast<int*>(smem + CH * GST * 4);   // [CH + pad] level pixel of each point of the pass, -1: outside the level
+    int* q_pix = rowpix + CH + TAB_PAD;                          // [128 + pad] source pixel of each query slot, -1: empty
+    float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP + TAB_PAD);
+    float* q_cy = q_cx + CORR_GROUP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lr = lane & 15, lg = lane >> 4;
+    const int n = item.z;
+    int b, u, v;
+    corr_cell_coords(a.g, item.x, &b, &u, &v);
+    u += a.g.u_min; v += a.g.v_min;
+    const int K = 2 * a.r + 1, KK = K * K, D = a.D;
+    if (tid < CORR_GROUP + TAB_PAD) {
+        int pix = -1;
+        float2 xy = make_float2(0.f, 0.f);
+        if (tid < n) { pix = a.perm[item.y + tid] - b * a.HW; xy = a.sorted_c[item.y + tid]; }
+        q_pix[tid] = pix;
+        if (tid < CORR_GROUP) { q_cx[tid] = xy.x; q_cy[tid] = xy.y; }
+    }
+    if (tid < TAB_PAD) rowpix[CH + tid] = -1;
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t r_f1 = rsrc_of(a.f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
+    const __amdgpu_buffer_rsrc_t r_d1 = rsrc_of(a.d_f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
+
+    for (int cg = 0; cg < D; cg += 256) {                        // channel groups of 256: 32 per wave
+        const int ch = cg + wave * (16 * NTW) + lr;              // this lane's channel of tile nt: ch + 16 * nt
+        const bool wave_on = cg + wave * (16 * NTW) < D;         // uniform; D is a multiple of 32
+        f32x4 acc1[NMT][NTW];
+#pragma unroll
+        for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) acc1[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int l = 0; l < a.L; ++l) {
+            const int Hl = a.Hl[l], Wl = a.Wl[l];
+            const int CXL = max((1 << CORR_LOG_CX) >> l, 1), CYL = max((1 << CORR_LOG_CY) >> l, 1);
+            const int WSX = CXL + K, WSY = CYL + K, NPTS = WSX * WSY;
+            const int xs = ((u << CORR_LOG_CX) >> l) - a.r, ys = ((v << CORR_LOG_CY) >> l) - a.r;
+            if (!(xs + WSX - 1 >= 0 && xs <= Wl - 1 && ys + WSY - 1 >= 0 && ys <= Hl - 1)) continue;   // all padding (uniform)
+            const __amdgpu_buffer_rsrc_t r_f2 = rsrc_of(a.f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
+            const __amdgpu_buffer_rsrc_t r_d2 = rsrc_of(a.d_f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
+            for (int r0 = 0; r0 < NPTS; r0 += CH) {
+                __syncthreads();                                 // the previous pass no longer reads G or rowpix
+                {
+                    float4* g4 = reinterpret_cast<float4*>(G);
+                    for (int i = tid; i < CH * GST / 4; i += NTI) g4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (tid < CH) {
+                        const int row = r0 + tid, wy = row / WSX, wx = row - wy * WSX;
+                        const int y = ys + wy, x = xs + wx;
+                        rowpix[tid] = (row < NPTS && y >= 0 && y < Hl && x >= 0 && x < Wl) ? y * Wl + x : -1;
+                    }
+                }
+                __syncthreads();
+                {
+                    // footprint weights into G: thread = (query, quarter of the footprint columns).  Point (pu, pv)
+                    // collects the taps (pu - du, pv - dv), du, dv in {0, 1}, with their corner weights; every
+                    // element of G has one writer, so G (and with it d f1) is the same bits on every call.
+                    const int q = tid & (CORR_GROUP - 1), part = tid >> 7;
+                    if (q < n) {
+                        const float inv = __uint_as_float((uint32_t)(127 - l) << 23);
+                        const float cxl = q_cx[q] * inv, cyl = q_cy[q] * inv;
+                        const float flx = floorf(cxl), fly = floorf(cyl);
+                        const float fx = cxl - flx, fy = cyl - fly;
+                        const int rx = (int)flx - a.r - xs, ry = (int)fly - a.r - ys;
+                        const float wx1 = fx * a.scale, wx0 = a.scale - wx1;
+                        const int p0 = part * (K + 1) / 4, p1 = (part + 1) * (K + 1) / 4;
+                        const float* dp = a.d_out + ((size_t)(b * a.L + l) * KK) * a.HW + q_pix[q];
+                        float* gq = G + q;
+                        for (int pu = p0; pu < p1; ++pu) {
+                            float tprev = 0.f;
+                            int rr = ry * WSX + rx + pu - r0;
+                            for (int pv = 0; pv <= K; ++pv) {
+                                float t = 0.f;
+                                if (pv < K) {
+                                    if (pu < K) t = dp[(size_t)(pu * K + pv) * a.HW] * wx0;
+                                    if (pu >= 1) t += dp[(size_t)((pu - 1) * K + pv) * a.HW] * wx1;
+                                }
+                                if ((unsigned)rr < (unsigned)CH) gq[rr * GST] = t + fy * (tprev - t);
+                                tprev = t;
+                                rr += WSX;
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
+                if (wave_on) {
+                    const int rows = min(CH, NPTS - r0);
+                    float bq[4][NTW];
+                    // d f1 += G^T x f2 rows.  k-step ks: points 4*ks + lg; the f2 loads run three steps ahead
+                    // (steps past the last one find -1 in the table and rows of zeros in G).
+                    const int nks = (rows + 3) >> 2;
+                    auto load_p = [&](int ks, float (&dst)[NTW]) {
+                        const int pix = rowpix[4 * ks + lg];
+                        const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
+#pragma unroll
+                        for (int nt = 0; nt < NTW; ++nt) dst[nt] = buf_load(r_f2, off + 64u * nt);
+                    };
+                    load_p(0, bq[0]); load_p(1, bq[1]); load_p(2, bq[2]);
+#pragma unroll 1
+                    for (int ks0 = 0; ks0 < nks; ks0 += 4) {
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) {
+                            const int ks = ks0 + s;
+                            load_p(ks + 3, bq[(s + 3) & 3]);
+                            const float* gr = G + (4 * ks + lg) * GST + lr;
+                            float af[NMT];
+#pragma unroll
+                            for (int mt = 0; mt < NMT; ++mt) af[mt] = gr[16 * mt];
+#pragma unroll
+                            for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+                                for (int nt = 0; nt < NTW; ++nt) acc1[mt][nt] = mma4(af[mt], bq[s][nt], acc1[mt][nt]);
+                        }
+                    }
+                    // d f2_l rows of this pass = G x f1: all MTC point tiles (rows past the window are zero in G).
+                    // k-step ks: queries 4*ks + lg, their f1 rows three steps ahead as well.
+                    f32x4 acc2[MTC][NTW];
+#pragma unroll
+                    for (int mt = 0; mt < MTC; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < NTW; ++nt) acc2[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    auto load_q = [&](int ks, float (&dst)[NTW]) {
+                        const int pix = q_pix[4 * ks + lg];
+                        const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
+#pragma unroll
+                        for (int nt = 0; nt < NTW; ++nt) dst[nt] = buf_load(r_f1, off + 64u * nt);
+                    };
+                    load_q(0, bq[0]); load_q(1, bq[1]); load_q(2, bq[2]);
+#pragma unroll 1
+                    for (int ks0 = 0; ks0 < NMT * 4; ks0 += 4) {
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) {
+                            const int ks = ks0 + s;
+                            load_q(ks + 3, bq[(s + 3) & 3]);
+                            const float* gc = G + lr * GST + 4 * ks + lg;
+                            float af[MTC];
+#pragma unroll
+                            for (int mt = 0; mt < MTC; ++mt) af[mt] = gc[16 * mt * GST];
+#pragma unroll
+                            for (int mt = 0; mt < MTC; ++mt)
+#pragma unroll
+                                for (int nt = 0; nt < NTW; ++nt) acc2[mt][nt] = mma4(af[mt], bq[s][nt], acc2[mt][nt]);
+                        }
+                    }
+#pragma unroll
+                    for (int mt = 0; mt < MTC; ++mt)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int pix = rowpix[16 * mt + 4 * lg + e];
+                            const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
+#pragma unroll
+                            for (int nt = 0; nt < NTW; ++nt)
+                                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(acc2[mt][nt][e], r_d2, (int)(off + 64u * nt), 0, 0);
+                        }
+                }
+            }
+        }
+        if (wave_on) {
+#pragma unroll
+            for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int pix = q_pix[16 * mt + 4 * lg + e];
+                    const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
+#pragma unroll
+                    for (int nt = 0; nt < NTW; ++nt)
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc1[mt][nt][e]), r_d1, (int)(off + 64u * nt), 0, 0);
+                }
+        }
+    }
+}
+
+__global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int k = corr_item_of_workgroup(blockIdx.x);
+    if (k >= *a.n_items) return;
+    const int4 item = a.items[k];
+    if (item.z <= 32) bwd_item_body<2>(a, smem, item);
+    else if (item.z <= 64) bwd_item_body<4>(a, smem, item);
+    else if (item.z <= 96) bwd_item_body<6>(a, smem, item);
+    else bwd_item_body<8>(a, smem, item);
+}
+
 // adjoint of the 2x2 mean: every pixel of the coarse level adds a quarter of its gradient to its four children
 __global__ __launch_bounds__(256) void bwd_unpool_kernel(const float* __restrict__ coarse, float* __restrict__ fine,
                                                          size_t n, int D, int Hc, int Wc, int Hf, int Wf) {
@@ -138,41 +373,61 @@ size_t corr_backward_workspace_floats(int B, int H, int W, int D, int L) {
 }
 
 hipError_t launch_backward(const corr_pyramid* p, const float* coords, const float* d_out, int r,
-                           float* d_fmap1, float* d_fmap2, float* ws, hipStream_t s) {
-    BwdArgs a;
+                           float* d_fmap1, float* d_fmap2, float* ws, int form, hipStream_t s) {
     const int HW = p->H * p->W;
-    a.f1 = p->f1_nhwc; a.coords = coords; a.d_out = d_out;
-    a.B = p->B; a.HW = HW; a.D = p->D; a.L = p->L; a.r = r;
-    a.scale = 1.0f / sqrtf((float)p->D);
     float* cur = ws;
-    a.d_f1 = cur; cur += (size_t)p->B * HW * p->D;
+    float* d_f1 = cur; cur += (size_t)p->B * HW * p->D;
+    float* d_f2[CORR_MAX_L] = {nullptr, nullptr, nullptr, nullptr};
     size_t lev_floats = 0;
-    for (int l = 0; l < CORR_MAX_L; ++l) {
-        a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr;
-        a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
-        a.d_f2[l] = nullptr;
-        if (l < p->L) {
-            a.d_f2[l] = cur;
-            const size_t n = (size_t)p->B * p->Hl[l] * p->Wl[l] * p->D;
-            cur += n; lev_floats += n;
-        }
+    for (int l = 0; l < p->L; ++l) {
+        d_f2[l] = cur;
+        const size_t n = (size_t)p->B * p->Hl[l] * p->Wl[l] * p->D;
+        cur += n; lev_floats += n;
     }
-    // the level gradients accumulate: they start at zero (a fill kernel, so the call can be graph-captured)
-    hipError_t e = launch_fill_i32(reinterpret_cast<int*>(a.d_f2[0]), 0, lev_floats, s);
-    if (e != hipSuccess) return e;
+    const float scale = 1.0f / sqrtf((float)p->D);
     const long long BN = (long long)p->B * HW;
-    hipLaunchKernelGGL(bwd_query_kernel, dim3((unsigned)((BN + BQ - 1) / BQ)), dim3(64 * BQ), 0, s, a);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipError_t e;
+    if (form == CORR_BACKWARD_ITEMS) {
+        // everything accumulates or keeps its zero (a fill kernel, so the call can be graph-captured)
+        if ((e = launch_fill_i32(reinterpret_cast<int*>(ws), 0, (size_t)p->B * HW * p->D + lev_floats, s)) != hipSuccess) return e;
+        LookupArgs q{coords, nullptr, r, 0, 0, 0};
+        if ((e = launch_binning(p, p->ws, q, s)) != hipSuccess) return e;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_item_kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, ITEM_LDS);
+        if (attr != hipSuccess) return attr;
+        BwdItemArgs a;
+        a.f1 = p->f1_nhwc; a.d_f1 = d_f1; a.d_out = d_out;
+        a.perm = p->ws.perm; a.sorted_c = p->ws.sorted_c; a.items = p->ws.items; a.n_items = p->ws.n_items;
+        a.B = p->B; a.HW = HW; a.D = p->D; a.L = p->L; a.r = r; a.g = p->grid; a.scale = scale;
+        for (int l = 0; l < CORR_MAX_L; ++l) {
+            a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr; a.d_f2[l] = d_f2[l];
+            a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
+        }
+        hipLaunchKernelGGL(bwd_item_kernel, dim3(corr_block_grid(p->ws.max_items)), dim3(NTI), ITEM_LDS, s, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else {
+        BwdArgs a;
+        a.f1 = p->f1_nhwc; a.coords = coords; a.d_out = d_out;
+        a.B = p->B; a.HW = HW; a.D = p->D; a.L = p->L; a.r = r; a.scale = scale;
+        a.d_f1 = d_f1;
+        for (int l = 0; l < CORR_MAX_L; ++l) {
+            a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr; a.d_f2[l] = d_f2[l];
+            a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
+        }
+        if ((e = launch_fill_i32(reinterpret_cast<int*>(d_f2[0]), 0, lev_floats, s)) != hipSuccess) return e;
+        hipLaunchKernelGGL(bwd_query_kernel, dim3((unsigned)((BN + BQ - 1) / BQ)), dim3(64 * BQ), 0, s, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     for (int l = p->L - 1; l >= 1; --l) {
         const size_t n = (size_t)p->B * p->Hl[l] * p->Wl[l] * p->D;
         const size_t blocks = (n + 255) / 256;
         hipLaunchKernelGGL(bwd_unpool_kernel, dim3((unsigned)(blocks < (1u << 20) ? blocks : (1u << 20))), dim3(256), 0, s,
-                           a.d_f2[l], a.d_f2[l - 1], n, p->D, p->Hl[l], p->Wl[l], p->Hl[l - 1], p->Wl[l - 1]);
+                           d_f2[l], d_f2[l - 1], n, p->D, p->Hl[l], p->Wl[l], p->Hl[l - 1], p->Wl[l - 1]);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     dim3 tg((HW + 31) / 32, (p->D + 31) / 32, p->B);
-    hipLaunchKernelGGL(bwd_to_nchw_kernel, tg, dim3(256), 0, s, a.d_f1, d_fmap1, HW, p->D);
+    hipLaunchKernelGGL(bwd_to_nchw_kernel, tg, dim3(256), 0, s, d_f1, d_fmap1, HW, p->D);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_to_nchw_kernel, tg, dim3(256), 0, s, a.d_f2[0], d_fmap2, HW, p->D);
+    hipLaunchKernelGGL(bwd_to_nchw_kernel, tg, dim3(256), 0, s, d_f2[0], d_fmap2, HW, p->D);
     return hipGetLastError();
 }

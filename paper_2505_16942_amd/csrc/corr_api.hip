@@ -86,7 +86,7 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
         for (int l = 0; l < L; ++l)
             need(dev_alloc(&p->f2_nhwc[l], (size_t)B * p->Hl[l] * p->Wl[l] * D, &p->bytes));
     }
-    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16)) {      // what block mode reads, and its binning workspace
+    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16)) {      // what block mode reads
         size_t px = 0;
         for (int l = 0; l < L; ++l) { p->f2_pix_base[l] = (int)px; px += (size_t)B * p->Hl[l] * p->Wl[l]; }
         p->f2_pix_total = (int)px;
@@ -98,6 +98,8 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
             need(dev_alloc(&p->f1_hi, BN * D, &p->bytes));
             need(dev_alloc(&p->f2_hi, px * D, &p->bytes));
         }
+    }
+    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16 | CORR_REP_F32)) {   // the planning workspace of block mode and of the gradient
         const int ncells = corr_ncells(p->grid, B);
         const WsLayout wl = corr_ws_layout((int)BN, ncells);
         unsigned char* mem = nullptr;
@@ -130,6 +132,7 @@ struct Profiler {
 
 // process-wide test knob (corr_debug_set_level_split)
 std::atomic<int> g_split_levels_max{CORR_SPLIT_LEVELS_MAX_QUERIES};
+std::atomic<int> g_backward_form{CORR_BACKWARD_ITEMS};
 
 hipError_t launch_block(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s) {
     return q.r == 1 ? launch_block_r1(p, ws, q, s)
@@ -481,9 +484,15 @@ corr_status corr_sample_backward(const corr_pyramid* pyr, const float* coords, c
     if (!(pyr->built & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
     if (workspace_bytes < corr_backward_workspace_floats(B, H, W, D, L) * sizeof(float)) return CORR_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0) return CORR_ERR_INVALID_ARG;
+    // the item form addresses one batch item's feature map through 31-bit byte offsets
+    if ((unsigned long long)H * W * D * 4ull >= (1ull << 31)) return CORR_ERR_UNSUPPORTED;
     const hipError_t e = launch_backward(pyr, coords, d_out, r, d_fmap1, d_fmap2, static_cast<float*>(workspace),
-                                         static_cast<hipStream_t>(stream));
+                                         g_backward_form.load(), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;
+}
+
+int corr_debug_set_backward_form(int form) {
+    return g_backward_form.exchange(form == CORR_BACKWARD_QUERIES ? CORR_BACKWARD_QUERIES : CORR_BACKWARD_ITEMS);
 }
 
 int corr_debug_set_level_split(int max_queries) {
