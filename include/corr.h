@@ -131,10 +131,17 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
  *   d_fmap1, d_fmap2 : device, fp32 [B, D, H, W], fully overwritten.  The gradient of the pooled levels
  *               is folded into d_fmap2 (adjoint of the 2x2 mean; a trailing odd row or column that the
  *               pooling dropped receives level 0's share only).
- *   workspace : device, at least corr_backward_workspace_bytes(B, H, W, D, L) bytes, 4-byte aligned,
- *               caller-owned; contents on entry are ignored, contents on return are scratch.
- * Enqueues kernels on `stream` and returns; allocates nothing.  fp32 throughout; d_fmap2 is accumulated
- * with floating-point atomics, so two calls agree to rounding, not bit for bit.
+ *   workspace : device, at least corr_backward_workspace_bytes(B, H, W, D, L) bytes, 16-byte aligned
+ *               (else CORR_ERR_INVALID_ARG), caller-owned; contents on entry are ignored, contents on return
+ *               are scratch.  It holds the channels-last gradients of fmap1 and of every level and a planning
+ *               workspace of the call's own: the pyramid is only read, so the call may run beside lookups
+ *               on the same pyramid.
+ * Enqueues kernels on `stream` and returns; allocates nothing.  The queries are binned into the forward
+ * pass's work items (a target cell and up to 128 of its queries); per item and level both gradients are
+ * fp32 matrix-core contractions over the item's window.  fp32 throughout.  d_fmap1 has the same bits on
+ * every call; d_fmap2 is accumulated with floating-point atomics, so two calls agree to rounding, not bit
+ * for bit.  Limits beyond corr_sample's: H*W*D*4 and H*W*(2r+1)^2*4 below 2^31 (one batch item's map and
+ * one level's planes of d_out are addressed with 31-bit byte offsets), else CORR_ERR_UNSUPPORTED.
  */
 size_t corr_backward_workspace_bytes(int B, int H, int W, int D, int L);
 corr_status corr_sample_backward(const corr_pyramid* pyr, const float* coords, const float* d_out,

@@ -123,7 +123,9 @@ constexpr int CH = 144;                     // window points per pass: level 2's
 constexpr int MTC = CH / 16;
 constexpr int NTW = 2;                      // 16-channel tiles per wave
 constexpr int TAB_PAD = 16;                 // the operand loads run three k-steps ahead: the tables end in invalid entries
-constexpr int ITEM_LDS = CH * GST * 4 + (CH + TAB_PAD) * 4 + (CORR_GROUP + TAB_PAD) * 4 + CORR_GROUP * 8;
+constexpr int MAXKK = (2 * CORR_R + 1) * (2 * CORR_R + 1);
+constexpr int TAPS_PER_THREAD = (MAXKK + NTI / CORR_GROUP - 1) / (NTI / CORR_GROUP);
+constexpr int ITEM_LDS = CH * GST * 4 + (CH + TAB_PAD) * 4 + (CORR_GROUP + TAB_PAD) * 4 + CORR_GROUP * 8 + MAXKK * CORR_GROUP * 4;
 constexpr unsigned BAD_OFF = 0x80000000u;   // beyond every buffer here (each is below 2 GiB)
 
 struct BwdItemArgs {
@@ -151,14 +153,69 @@ __device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, unsigned off
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
 }
 
-// NMT: 16-query tiles the item fills (its query count rounded up to 32 or more: 2, 4, 6 or 8)
+// d f2_l rows of one pass = G x f1 for MT 16-point tiles (rows past the window are zero in G), then out through
+// atomics.  k-step ks takes queries 4*ks + lg.  Software pipeline, pinned by the scheduling barriers: the f1 values
+// of step ks + 3, the table entry of step ks + 4 and the G fragments of step ks + 1 are on their way while the
+// matrix cores work on step ks.
+template <int NMT, int MT>
+__device__ __forceinline__ void rows_gradient(const float* G, const unsigned* rowoff, const unsigned* q_off,
+                                              __amdgpu_buffer_rsrc_t r_f1, __amdgpu_buffer_rsrc_t r_d2,
+                                              unsigned ch4, int lr, int lg) {
+    f32x4 acc2[MT][NTW];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) acc2[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float bq[4][NTW], af[2][MT];
+    auto load_b = [&](unsigned off, float (&dst)[NTW]) {
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) dst[nt] = buf_load(r_f1, off + ch4 + 64u * nt);
+    };
+    auto read_a = [&](int ks, float (&dst)[MT]) {
+        const float* gc = G + lr * GST + 4 * ks + lg;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) dst[mt] = gc[16 * mt * GST];
+    };
+    load_b(q_off[lg], bq[0]); load_b(q_off[4 + lg], bq[1]); load_b(q_off[8 + lg], bq[2]);
+    unsigned off_next = q_off[12 + lg];
+    read_a(0, af[0]);
+#pragma unroll 1
+    for (int ks0 = 0; ks0 < NMT * 4; ks0 += 4) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int ks = ks0 + s;
+            load_b(off_next, bq[(s + 3) & 3]);
+            off_next = q_off[4 * (ks + 4) + lg];
+            read_a(ks + 1, af[(s + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) acc2[mt][nt] = mma4(af[s & 1][mt], bq[s][nt], acc2[mt][nt]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const unsigned off = rowoff[16 * mt + 4 * lg + e] + ch4;
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt)
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(acc2[mt][nt][e], r_d2, (int)(off + 64u * nt), 0, 0);
+        }
+}
+
+// NMT: 16-query tiles the item fills (1..8)
 template <int NMT>
 __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item) {
     float* G = reinterpret_cast<float*>(smem);                   // [CH][GST]
-    int* rowpix = reinterpret_cast<int*>(smem + CH * GST * 4);   // [CH + pad] level pixel of each point of the pass, -1: outside the level
-    int* q_pix = rowpix + CH + TAB_PAD;                          // [128 + pad] source pixel of each query slot, -1: empty
-    float* q_cx = reinterpret_cast<float*>(q_pix + CORR_GROUP + TAB_PAD);
+    // byte offset of the feature row (pixel * D * 4) of each point of the pass / of each query slot; BAD_OFF: outside the level / empty
+    unsigned* rowoff = reinterpret_cast<unsigned*>(smem + CH * GST * 4);   // [CH + pad]
+    unsigned* q_off = rowoff + CH + TAB_PAD;                                // [128 + pad]
+    float* q_cx = reinterpret_cast<float*>(q_off + CORR_GROUP + TAB_PAD);
     float* q_cy = q_cx + CORR_GROUP;
+    float* taps = q_cy + CORR_GROUP;                             // [K*K][128] tap gradients of the level in work, one column per query
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 15, lg = lane >> 4;
     const int n = item.z;
@@ -170,10 +227,10 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
         int pix = -1;
         float2 xy = make_float2(0.f, 0.f);
         if (tid < n) { pix = a.perm[item.y + tid] - b * a.HW; xy = a.sorted_c[item.y + tid]; }
-        q_pix[tid] = pix;
+        q_off[tid] = pix >= 0 ? (unsigned)pix * (unsigned)D * 4u : BAD_OFF;
         if (tid < CORR_GROUP) { q_cx[tid] = xy.x; q_cy[tid] = xy.y; }
     }
-    if (tid < TAB_PAD) rowpix[CH + tid] = -1;
+    if (tid < TAB_PAD) rowoff[CH + tid] = BAD_OFF;
     __syncthreads();
     const __amdgpu_buffer_rsrc_t r_f1 = rsrc_of(a.f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
     const __amdgpu_buffer_rsrc_t r_d1 = rsrc_of(a.d_f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
@@ -195,15 +252,37 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
             if (!(xs + WSX - 1 >= 0 && xs <= Wl - 1 && ys + WSY - 1 >= 0 && ys <= Hl - 1)) continue;   // all padding (uniform)
             const __amdgpu_buffer_rsrc_t r_f2 = rsrc_of(a.f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
             const __amdgpu_buffer_rsrc_t r_d2 = rsrc_of(a.d_f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
+            {
+                // this level's tap gradients: all loads of a thread in flight at once, then into LDS (the first
+                // pass's barriers order them before the reads; the barrier here, after the previous level's)
+                const int q = tid & (CORR_GROUP - 1), part = tid >> 7;
+                float tv[TAPS_PER_THREAD];
+                // the level's K*K planes of this batch item as one buffer: the lane's pixel is the vector offset,
+                // the tap's plane (the same for a whole wave) a scalar offset
+                const __amdgpu_buffer_rsrc_t r_do = rsrc_of(a.d_out + ((size_t)(b * a.L + l) * KK) * a.HW, (size_t)KK * a.HW);
+                const unsigned poff = q < n ? q_off[q] / (unsigned)D : BAD_OFF;      // pixel * 4
+                const int wpart = __builtin_amdgcn_readfirstlane(part);
+#pragma unroll
+                for (int i = 0; i < TAPS_PER_THREAD; ++i) {
+                    const int t = min(wpart + i * (NTI / CORR_GROUP), KK - 1);
+                    tv[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_do, (int)poff, t * a.HW * 4, 0));
+                }
+                __syncthreads();                                 // the previous level's last pass no longer reads taps
+#pragma unroll
+                for (int i = 0; i < TAPS_PER_THREAD; ++i) {
+                    const int t = part + i * (NTI / CORR_GROUP);
+                    if (t < KK) taps[t * CORR_GROUP + q] = tv[i];
+                }
+            }
             for (int r0 = 0; r0 < NPTS; r0 += CH) {
-                __syncthreads();                                 // the previous pass no longer reads G or rowpix
+                __syncthreads();                                 // the previous pass no longer reads G or rowoff
                 {
                     float4* g4 = reinterpret_cast<float4*>(G);
                     for (int i = tid; i < CH * GST / 4; i += NTI) g4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (tid < CH) {
                         const int row = r0 + tid, wy = row / WSX, wx = row - wy * WSX;
                         const int y = ys + wy, x = xs + wx;
-                        rowpix[tid] = (row < NPTS && y >= 0 && y < Hl && x >= 0 && x < Wl) ? y * Wl + x : -1;
+                        rowoff[tid] = (row < NPTS && y >= 0 && y < Hl && x >= 0 && x < Wl) ? (unsigned)(y * Wl + x) * (unsigned)D * 4u : BAD_OFF;
                     }
                 }
                 __syncthreads();
@@ -220,7 +299,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                         const int rx = (int)flx - a.r - xs, ry = (int)fly - a.r - ys;
                         const float wx1 = fx * a.scale, wx0 = a.scale - wx1;
                         const int p0 = part * (K + 1) / 4, p1 = (part + 1) * (K + 1) / 4;
-                        const float* dp = a.d_out + ((size_t)(b * a.L + l) * KK) * a.HW + q_pix[q];
+                        const float* dp = taps + q;
                         float* gq = G + q;
                         for (int pu = p0; pu < p1; ++pu) {
                             float tprev = 0.f;
@@ -228,8 +307,8 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                             for (int pv = 0; pv <= K; ++pv) {
                                 float t = 0.f;
                                 if (pv < K) {
-                                    if (pu < K) t = dp[(size_t)(pu * K + pv) * a.HW] * wx0;
-                                    if (pu >= 1) t += dp[(size_t)((pu - 1) * K + pv) * a.HW] * wx1;
+                                    if (pu < K) t = dp[(pu * K + pv) * CORR_GROUP] * wx0;
+                                    if (pu >= 1) t += dp[((pu - 1) * K + pv) * CORR_GROUP] * wx1;
                                 }
                                 if ((unsigned)rr < (unsigned)CH) gq[rr * GST] = t + fy * (tprev - t);
                                 tprev = t;
@@ -241,73 +320,50 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                 __syncthreads();
                 if (wave_on) {
                     const int rows = min(CH, NPTS - r0);
+                    const unsigned ch4 = (unsigned)ch * 4u;
                     float bq[4][NTW];
-                    // d f1 += G^T x f2 rows.  k-step ks: points 4*ks + lg; the f2 loads run three steps ahead
-                    // (steps past the last one find -1 in the table and rows of zeros in G).
+                    // d f1 += G^T x f2 rows.  k-step ks takes points 4*ks + lg.  Software pipeline, pinned by the
+                    // scheduling barriers: the f2 values of step ks + 3, the table entry of step ks + 4 and the G
+                    // fragments of step ks + 1 are on their way while the matrix cores work on step ks.  Steps
+                    // past the last one find BAD_OFF in the table (zeros) and rows of zeros in G.
                     const int nks = (rows + 3) >> 2;
-                    auto load_p = [&](int ks, float (&dst)[NTW]) {
-                        const int pix = rowpix[4 * ks + lg];
-                        const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
+                    {
+                        float af[2][NMT];
+                        auto load_b = [&](unsigned off, float (&dst)[NTW]) {
 #pragma unroll
-                        for (int nt = 0; nt < NTW; ++nt) dst[nt] = buf_load(r_f2, off + 64u * nt);
-                    };
-                    load_p(0, bq[0]); load_p(1, bq[1]); load_p(2, bq[2]);
-#pragma unroll 1
-                    for (int ks0 = 0; ks0 < nks; ks0 += 4) {
-#pragma unroll
-                        for (int s = 0; s < 4; ++s) {
-                            const int ks = ks0 + s;
-                            load_p(ks + 3, bq[(s + 3) & 3]);
+                            for (int nt = 0; nt < NTW; ++nt) dst[nt] = buf_load(r_f2, off + ch4 + 64u * nt);
+                        };
+                        auto read_a = [&](int ks, float (&dst)[NMT]) {
                             const float* gr = G + (4 * ks + lg) * GST + lr;
-                            float af[NMT];
 #pragma unroll
-                            for (int mt = 0; mt < NMT; ++mt) af[mt] = gr[16 * mt];
-#pragma unroll
-                            for (int mt = 0; mt < NMT; ++mt)
-#pragma unroll
-                                for (int nt = 0; nt < NTW; ++nt) acc1[mt][nt] = mma4(af[mt], bq[s][nt], acc1[mt][nt]);
-                        }
-                    }
-                    // d f2_l rows of this pass = G x f1: all MTC point tiles (rows past the window are zero in G).
-                    // k-step ks: queries 4*ks + lg, their f1 rows three steps ahead as well.
-                    f32x4 acc2[MTC][NTW];
-#pragma unroll
-                    for (int mt = 0; mt < MTC; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < NTW; ++nt) acc2[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    auto load_q = [&](int ks, float (&dst)[NTW]) {
-                        const int pix = q_pix[4 * ks + lg];
-                        const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
-#pragma unroll
-                        for (int nt = 0; nt < NTW; ++nt) dst[nt] = buf_load(r_f1, off + 64u * nt);
-                    };
-                    load_q(0, bq[0]); load_q(1, bq[1]); load_q(2, bq[2]);
+                            for (int mt = 0; mt < NMT; ++mt) dst[mt] = gr[16 * mt];
+                        };
+                        load_b(rowoff[lg], bq[0]); load_b(rowoff[4 + lg], bq[1]); load_b(rowoff[8 + lg], bq[2]);
+                        unsigned off_next = rowoff[12 + lg];
+                        read_a(0, af[0]);
 #pragma unroll 1
-                    for (int ks0 = 0; ks0 < NMT * 4; ks0 += 4) {
+                        for (int ks0 = 0; ks0 < nks; ks0 += 4) {
 #pragma unroll
-                        for (int s = 0; s < 4; ++s) {
-                            const int ks = ks0 + s;
-                            load_q(ks + 3, bq[(s + 3) & 3]);
-                            const float* gc = G + lr * GST + 4 * ks + lg;
-                            float af[MTC];
+                            for (int s = 0; s < 4; ++s) {
+                                const int ks = ks0 + s;
+                                load_b(off_next, bq[(s + 3) & 3]);
+                                off_next = rowoff[4 * (ks + 4) + lg];
+                                read_a(ks + 1, af[(s + 1) & 1]);
+                                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                            for (int mt = 0; mt < MTC; ++mt) af[mt] = gc[16 * mt * GST];
+                                for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
-                            for (int mt = 0; mt < MTC; ++mt)
-#pragma unroll
-                                for (int nt = 0; nt < NTW; ++nt) acc2[mt][nt] = mma4(af[mt], bq[s][nt], acc2[mt][nt]);
+                                    for (int nt = 0; nt < NTW; ++nt) acc1[mt][nt] = mma4(af[s & 1][mt], bq[s][nt], acc1[mt][nt]);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
                         }
                     }
-#pragma unroll
-                    for (int mt = 0; mt < MTC; ++mt)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int pix = rowpix[16 * mt + 4 * lg + e];
-                            const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
-#pragma unroll
-                            for (int nt = 0; nt < NTW; ++nt)
-                                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(acc2[mt][nt][e], r_d2, (int)(off + 64u * nt), 0, 0);
-                        }
+                    // d f2_l rows of this pass = G x f1, over as many 16-point tiles as the pass has rows (rounded up to odd)
+                    const int tiles = (rows + 15) >> 4;
+                    if (tiles <= 3) rows_gradient<NMT, 3>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
+                    else if (tiles <= 5) rows_gradient<NMT, 5>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
+                    else if (tiles <= 7) rows_gradient<NMT, 7>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
+                    else rows_gradient<NMT, MTC>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
                 }
             }
         }
@@ -316,8 +372,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
             for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int pix = q_pix[16 * mt + 4 * lg + e];
-                    const unsigned off = pix >= 0 ? ((unsigned)pix * (unsigned)D + (unsigned)ch) * 4u : BAD_OFF;
+                    const unsigned off = q_off[16 * mt + 4 * lg + e] + (unsigned)ch * 4u;
 #pragma unroll
                     for (int nt = 0; nt < NTW; ++nt)
                         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc1[mt][nt][e]), r_d1, (int)(off + 64u * nt), 0, 0);
@@ -331,24 +386,15 @@ __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
     const int k = corr_item_of_workgroup(blockIdx.x);
     if (k >= *a.n_items) return;
     const int4 item = a.items[k];
-    if (item.z <= 32) bwd_item_body<2>(a, smem, item);
-    else if (item.z <= 64) bwd_item_body<4>(a, smem, item);
-    else if (item.z <= 96) bwd_item_body<6>(a, smem, item);
-    else bwd_item_body<8>(a, smem, item);
-}
-
-// adjoint of the 2x2 mean: every pixel of the coarse level adds a quarter of its gradient to its four children
-__global__ __launch_bounds__(256) void bwd_unpool_kernel(const float* __restrict__ coarse, float* __restrict__ fine,
-                                                         size_t n, int D, int Hc, int Wc, int Hf, int Wf) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        const int ch = (int)(i % D);
-        size_t pix = i / D;
-        const int u = (int)(pix % Wc); pix /= Wc;
-        const int v = (int)(pix % Hc);
-        const size_t b = pix / Hc;
-        const float t = 0.25f * coarse[i];
-        float* f = fine + ((b * Hf + 2 * v) * (size_t)Wf + 2 * u) * D + ch;
-        f[0] += t; f[D] += t; f[(size_t)Wf * D] += t; f[(size_t)Wf * D + D] += t;
+    switch ((item.z + 15) >> 4) {                          // uniform
+        case 1: bwd_item_body<1>(a, smem, item); break;
+        case 2: bwd_item_body<2>(a, smem, item); break;
+        case 3: bwd_item_body<3>(a, smem, item); break;
+        case 4: bwd_item_body<4>(a, smem, item); break;
+        case 5: bwd_item_body<5>(a, smem, item); break;
+        case 6: bwd_item_body<6>(a, smem, item); break;
+        case 7: bwd_item_body<7>(a, smem, item); break;
+        default: bwd_item_body<8>(a, smem, item); break;
     }
 }
 
@@ -364,12 +410,54 @@ __global__ __launch_bounds__(256) void bwd_to_nchw_kernel(const float* __restric
         if (d0 + r < D && p0 + tx < HW) dst[((size_t)b * D + d0 + r) * HW + p0 + tx] = tile[tx][r];
 }
 
+// d_fmap2 from the levels' gradients, channels-last to NCHW in the same pass.  Adjoint of the 2x2 mean: a pixel of
+// level l - 1 receives a quarter of its parent's gradient at level l, if it has a parent (a trailing odd row or
+// column that the pooling dropped has none, and then none at the deeper levels either).  For a level-0 pixel that
+// is the nested sum d0 + (d1 + (d2 + d3 / 4) / 4) / 4 along its chain of parents, evaluated from the deepest level.
+struct GatherArgs {
+    const float* d[CORR_MAX_L];
+    int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
+    int L, D, W, HW;
+};
+__global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, float* __restrict__ dst) {
+    __shared__ float tile[32][33];
+    const int b = blockIdx.z, p0 = blockIdx.x * 32, d0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int r = ty; r < 32; r += 8) {
+        const int p = p0 + r, ch = d0 + tx;
+        if (p < g.HW && ch < g.D) {
+            const int y = p / g.W, x = p - y * g.W;
+            float t = 0.f;
+            for (int l = g.L - 1; l >= 1; --l) {
+                const int yy = y >> l, xx = x >> l;
+                if (yy < g.Hl[l] && xx < g.Wl[l])
+                    t = g.d[l][(((size_t)b * g.Hl[l] + yy) * g.Wl[l] + xx) * g.D + ch] + 0.25f * t;
+            }
+            tile[r][tx] = g.d[0][((size_t)b * g.HW + p) * g.D + ch] + 0.25f * t;
+        }
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8)
+        if (d0 + r < g.D && p0 + tx < g.HW) dst[((size_t)b * g.D + d0 + r) * g.HW + p0 + tx] = tile[tx][r];
+}
+
 }  // namespace
 
 size_t corr_backward_workspace_floats(int B, int H, int W, int D, int L) {
     size_t px = 0;
     for (int l = 0; l < L; ++l) px += (size_t)(H >> l) * (W >> l);
     return ((size_t)B * H * W + (size_t)B * px) * D;
+}
+
+// gradient arrays (rounded up to 256 bytes), then a planning workspace like the pyramid's (the call bins the
+// queries itself and leaves the pyramid's own workspace alone)
+static size_t grad_bytes(int B, int H, int W, int D, int L) {
+    return (corr_backward_workspace_floats(B, H, W, D, L) * sizeof(float) + 255) & ~(size_t)255;
+}
+size_t corr_backward_workspace_bytes_internal(int B, int H, int W, int D, int L) {
+    CellGrid g;
+    corr_fill_grid(&g, H, W, L);
+    return grad_bytes(B, H, W, D, L) + corr_ws_layout(B * H * W, corr_ncells(g, B)).total;
 }
 
 hipError_t launch_backward(const corr_pyramid* p, const float* coords, const float* d_out, int r,
@@ -390,20 +478,25 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
     if (form == CORR_BACKWARD_ITEMS) {
         // everything accumulates or keeps its zero (a fill kernel, so the call can be graph-captured)
         if ((e = launch_fill_i32(reinterpret_cast<int*>(ws), 0, (size_t)p->B * HW * p->D + lev_floats, s)) != hipSuccess) return e;
+        const BinWs bws = corr_ws_carve(reinterpret_cast<char*>(ws) + grad_bytes(p->B, p->H, p->W, p->D, p->L), (int)BN,
+                                        corr_ncells(p->grid, p->B));
+        // the bin and item counters start at zero; everything else in the planning workspace is written before it is read
+        if ((e = launch_fill_i32(bws.bin_count, 0, (size_t)bws.nbins, s)) != hipSuccess) return e;
+        if ((e = launch_fill_i32(bws.n_items, 0, CORR_NCOUNTERS, s)) != hipSuccess) return e;
         LookupArgs q{coords, nullptr, r, 0, 0, 0};
-        if ((e = launch_binning(p, p->ws, q, s)) != hipSuccess) return e;
+        if ((e = launch_binning(p, bws, q, s)) != hipSuccess) return e;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_item_kernel),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, ITEM_LDS);
         if (attr != hipSuccess) return attr;
         BwdItemArgs a;
         a.f1 = p->f1_nhwc; a.d_f1 = d_f1; a.d_out = d_out;
-        a.perm = p->ws.perm; a.sorted_c = p->ws.sorted_c; a.items = p->ws.items; a.n_items = p->ws.n_items;
+        a.perm = bws.perm; a.sorted_c = bws.sorted_c; a.items = bws.items; a.n_items = bws.n_items;
         a.B = p->B; a.HW = HW; a.D = p->D; a.L = p->L; a.r = r; a.g = p->grid; a.scale = scale;
         for (int l = 0; l < CORR_MAX_L; ++l) {
             a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr; a.d_f2[l] = d_f2[l];
             a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
         }
-        hipLaunchKernelGGL(bwd_item_kernel, dim3(corr_block_grid(p->ws.max_items)), dim3(NTI), ITEM_LDS, s, a);
+        hipLaunchKernelGGL(bwd_item_kernel, dim3(corr_block_grid(bws.max_items)), dim3(NTI), ITEM_LDS, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     } else {
         BwdArgs a;
@@ -418,16 +511,12 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
         hipLaunchKernelGGL(bwd_query_kernel, dim3((unsigned)((BN + BQ - 1) / BQ)), dim3(64 * BQ), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    for (int l = p->L - 1; l >= 1; --l) {
-        const size_t n = (size_t)p->B * p->Hl[l] * p->Wl[l] * p->D;
-        const size_t blocks = (n + 255) / 256;
-        hipLaunchKernelGGL(bwd_unpool_kernel, dim3((unsigned)(blocks < (1u << 20) ? blocks : (1u << 20))), dim3(256), 0, s,
-                           d_f2[l], d_f2[l - 1], n, p->D, p->Hl[l], p->Wl[l], p->Hl[l - 1], p->Wl[l - 1]);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
     dim3 tg((HW + 31) / 32, (p->D + 31) / 32, p->B);
     hipLaunchKernelGGL(bwd_to_nchw_kernel, tg, dim3(256), 0, s, d_f1, d_fmap1, HW, p->D);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_to_nchw_kernel, tg, dim3(256), 0, s, d_f2[0], d_fmap2, HW, p->D);
+    GatherArgs ga;
+    for (int l = 0; l < CORR_MAX_L; ++l) { ga.d[l] = d_f2[l]; ga.Hl[l] = p->Hl[l]; ga.Wl[l] = p->Wl[l]; }
+    ga.L = p->L; ga.D = p->D; ga.W = p->W; ga.HW = HW;
+    hipLaunchKernelGGL(bwd_gather_nchw_kernel, tg, dim3(256), 0, s, ga, d_fmap2);
     return hipGetLastError();
 }

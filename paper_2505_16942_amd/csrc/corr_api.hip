@@ -86,7 +86,7 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
         for (int l = 0; l < L; ++l)
             need(dev_alloc(&p->f2_nhwc[l], (size_t)B * p->Hl[l] * p->Wl[l] * D, &p->bytes));
     }
-    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16)) {      // what block mode reads
+    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16)) {      // what block mode reads, and its binning workspace
         size_t px = 0;
         for (int l = 0; l < L; ++l) { p->f2_pix_base[l] = (int)px; px += (size_t)B * p->Hl[l] * p->Wl[l]; }
         p->f2_pix_total = (int)px;
@@ -98,8 +98,6 @@ corr_status create(int B, int H, int W, int D, int L, unsigned reps, corr_pyrami
             need(dev_alloc(&p->f1_hi, BN * D, &p->bytes));
             need(dev_alloc(&p->f2_hi, px * D, &p->bytes));
         }
-    }
-    if (reps & (CORR_REP_SPLIT | CORR_REP_BF16 | CORR_REP_F32)) {   // the planning workspace of block mode and of the gradient
         const int ncells = corr_ncells(p->grid, B);
         const WsLayout wl = corr_ws_layout((int)BN, ncells);
         unsigned char* mem = nullptr;
@@ -472,7 +470,7 @@ corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32
 
 size_t corr_backward_workspace_bytes(int B, int H, int W, int D, int L) {
     if (check_dims(B, H, W, D, L) != CORR_OK) return 0;
-    return corr_backward_workspace_floats(B, H, W, D, L) * sizeof(float);
+    return corr_backward_workspace_bytes_internal(B, H, W, D, L);
 }
 
 corr_status corr_sample_backward(const corr_pyramid* pyr, const float* coords, const float* d_out,
@@ -482,10 +480,11 @@ corr_status corr_sample_backward(const corr_pyramid* pyr, const float* coords, c
     corr_status st = check_lookup_args(pyr, coords, d_out, B, H, W, D, L, r);
     if (st != CORR_OK) return st;
     if (!(pyr->built & CORR_REP_F32)) return CORR_ERR_MISSING_REP;
-    if (workspace_bytes < corr_backward_workspace_floats(B, H, W, D, L) * sizeof(float)) return CORR_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0) return CORR_ERR_INVALID_ARG;
-    // the item form addresses one batch item's feature map through 31-bit byte offsets
+    if (workspace_bytes < corr_backward_workspace_bytes_internal(B, H, W, D, L)) return CORR_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return CORR_ERR_INVALID_ARG;
+    // the item form addresses one batch item's feature map, and one level's planes of d_out, through 31-bit byte offsets
     if ((unsigned long long)H * W * D * 4ull >= (1ull << 31)) return CORR_ERR_UNSUPPORTED;
+    if ((unsigned long long)H * W * (2 * r + 1) * (2 * r + 1) * 4ull >= (1ull << 31)) return CORR_ERR_UNSUPPORTED;
     const hipError_t e = launch_backward(pyr, coords, d_out, r, d_fmap1, d_fmap2, static_cast<float*>(workspace),
                                          g_backward_form.load(), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;

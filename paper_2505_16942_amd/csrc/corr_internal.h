@@ -192,7 +192,8 @@ hipError_t launch_block_r3(const corr_pyramid* p, const BinWs& ws, const LookupA
 hipError_t launch_block_r4(const corr_pyramid* p, const BinWs& ws, const LookupArgs& q, hipStream_t s);
 hipError_t launch_ondemand(const corr_pyramid* p, const LookupArgs& q, hipStream_t s);
 // gradient of the lookup (backward.hip): `ws` holds corr_backward_workspace_floats() floats
-size_t corr_backward_workspace_floats(int B, int H, int W, int D, int L);
+size_t corr_backward_workspace_floats(int B, int H, int W, int D, int L);      // the gradient arrays
+size_t corr_backward_workspace_bytes_internal(int B, int H, int W, int D, int L);   // those and a planning workspace of its own
 hipError_t launch_backward(const corr_pyramid* p, const float* coords, const float* d_out, int r,
                            float* d_fmap1, float* d_fmap2, float* ws, int form, hipStream_t s);
 hipError_t launch_fullvol_build(const corr_pyramid* p, hipStream_t s);
