@@ -20,6 +20,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+PEAK_FP32_MFMA_TFS = 157.3    # MI355X dense fp32 MFMA
 
 
 def kernel_source_sha() -> str:
@@ -45,6 +46,8 @@ def bench_backward(args, cb, synth, torch, np) -> int:
     ws = torch.empty(cb.corr_backward_workspace_bytes(B, H, W, D, L) // 4, device=dev)
     g1 = torch.empty_like(t1)
     g2 = torch.empty_like(t1)
+    form = cb.CORR_BACKWARD_QUERIES if args.backward_form == "queries" else cb.CORR_BACKWARD_ITEMS
+    cb.corr_debug_set_backward_form(form)
     for _ in range(max(args.warmup, 1)):
         cb.corr_sample_backward(pyr, tc, d_out, r=r, d_fmap1=g1, d_fmap2=g2, workspace=ws)
     torch.cuda.synchronize()
@@ -53,25 +56,42 @@ def bench_backward(args, cb, synth, torch, np) -> int:
         cb.corr_sample_backward(pyr, tc, d_out, r=r, d_fmap1=g1, d_fmap2=g2, workspace=ws)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - tb) / args.steps
+    cb.corr_debug_set_backward_form(cb.CORR_BACKWARD_ITEMS)
     taps = B * N * L * K * K
     npyr = sum((H >> l) * (W >> l) for l in range(L))
     # algorithmic HBM bytes: d_out, fmap1 and every pyramid pixel (fp32) read once, both gradients written once
     bytes_alg = B * (taps // B * 4 + N * D * 4 + npyr * D * 4 + N * 8 + 2 * N * D * 4)
-    # what bounds this form: one float atomic per (query-level, footprint point inside the level, channel)
-    atomics = float(B * N * L * (K + 1) ** 2 * D)
     gbs = bytes_alg / dt / 1e9
+    # the item form's two dense contractions: every query against every point of its cell's window, per level
+    win = sum((max(16 >> l, 1) + K) * (max(8 >> l, 1) + K) for l in range(L))
+    flops_dense = 4.0 * B * N * win * D
+    flops_footprint = 4.0 * B * N * L * (K + 1) ** 2 * D       # what the gradient needs at the least
+    tfs = flops_dense / dt / 1e12
+    if form == cb.CORR_BACKWARD_ITEMS:
+        roof = {"bound": "mfma", "achieved": round(tfs, 2), "peak": PEAK_FP32_MFMA_TFS, "unit": "TFLOP/s",
+                "frac": round(tfs / PEAK_FP32_MFMA_TFS, 4), "traffic": None,
+                "kernel": "bwd_item_kernel (per work item and level: G^T x f2 rows and G x f1 rows on fp32 MFMA, "
+                          "window rows of d f2 out through float atomics); the time is the whole call's",
+                "flops_per_call": flops_dense, "footprint_flops_per_call": flops_footprint,
+                "hbm": {"achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                        "algorithmic_bytes_per_call": bytes_alg},
+                "note": "flops = 4 * queries * window points of the cell (%d over the levels) * D, unpadded; "
+                        "peak = dense fp32 MFMA" % win}
+    else:
+        atomics = float(B * N * L * (K + 1) ** 2 * D)
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                "kernel": "bwd_query_kernel (one wave per query, float atomics into the level gradients)",
+                "algorithmic_bytes_per_launch": bytes_alg,
+                "note": "the one-wave-per-query form: its time is the atomics', at most %.3g of them per call, "
+                        "%.0f G/s here" % (atomics, atomics / dt / 1e9)}
     result = {
         "metric": "correlation lookup gradient, tap gradients/s (queries x L x 81 taps)", "value": taps / dt,
         "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: B=%d fmap [%d,%d,%d,%d] L=%d r=%d; step = one corr_sample_backward"
-                               % (args.config, B, B, D, H, W, L, r), "seed": cfg["seed"]},
-        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
-                     "kernel": "bwd_query_kernel (one wave per query, float atomics into the level gradients)",
-                     "algorithmic_bytes_per_launch": bytes_alg,
-                     "note": "the on-demand form: its time is the atomics', at most %.3g of them per call, "
-                             "%.0f G/s here" % (atomics, atomics / dt / 1e9)},
+        "config": {"workload": "%s: B=%d fmap [%d,%d,%d,%d] L=%d r=%d; step = one corr_sample_backward (%s form)"
+                               % (args.config, B, B, D, H, W, L, r, args.backward_form), "seed": cfg["seed"]},
+        "roofline": roof,
     }
     pyr.destroy()
     print(json.dumps(result))
@@ -100,6 +120,8 @@ def main() -> int:
     ap.add_argument("--backward", action="store_true",
                     help="time the gradient of the lookup (corr_sample_backward) instead: a step = one call on the "
                          "workload's first coordinates; its own JSON line")
+    ap.add_argument("--backward-form", default="items", choices=["items", "queries"],
+                    help="with --backward: the work-item form on the matrix cores (default) or the earlier one-wave-per-query form")
     ap.add_argument("--compare-modes", action="store_true",
                     help="additionally time the on-demand and full-volume reference modes (one lookup each)")
     args = ap.parse_args()

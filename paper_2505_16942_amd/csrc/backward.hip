@@ -123,8 +123,7 @@ constexpr int CH = 144;                     // window points per pass: level 2's
 constexpr int MTC = CH / 16;
 constexpr int NTW = 2;                      // 16-channel tiles per wave
 constexpr int TAB_PAD = 16;                 // the operand loads run three k-steps ahead: the tables end in invalid entries
-constexpr int MAXKK = (2 * CORR_R + 1) * (2 * CORR_R + 1);
-constexpr int TAPS_PER_THREAD = (MAXKK + NTI / CORR_GROUP - 1) / (NTI / CORR_GROUP);
+constexpr int MAXKK = MAXK * MAXK;
 constexpr int ITEM_LDS = CH * GST * 4 + (CH + TAB_PAD) * 4 + (CORR_GROUP + TAB_PAD) * 4 + CORR_GROUP * 8 + MAXKK * CORR_GROUP * 4;
 constexpr unsigned BAD_OFF = 0x80000000u;   // beyond every buffer here (each is below 2 GiB)
 
@@ -142,12 +141,22 @@ struct BwdItemArgs {
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     CellGrid g;
     float scale;
+#ifdef CORR_TRACE
+    long long* trace;
+#endif
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ f32x4 mma4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const float* base, size_t floats) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)(unsigned)(floats * 4), 0x00020000);
+}
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+// 4 bytes per lane from a buffer straight into LDS at lds_base + lane * 4 (lds_base, the resource and soff uniform).
+// A lane whose offset lies beyond the resource's size writes zero.
+__device__ __forceinline__ void dma4(i32x4 rsrc, unsigned lds_base, unsigned voff, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
 __device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, unsigned off) {
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
@@ -196,7 +205,7 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
         }
     }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const unsigned off = rowoff[16 * mt + 4 * lg + e] + ch4;
@@ -204,9 +213,18 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
             for (int nt = 0; nt < NTW; ++nt)
                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(acc2[mt][nt][e], r_d2, (int)(off + 64u * nt), 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);                   // one tile's table reads at a time (left alone, all are hoisted)
+    }
 }
 
 // NMT: 16-query tiles the item fills (1..8)
+#ifdef CORR_TRACE
+// trace builds: thread 0 adds up the 100 MHz wall clock per phase (a barrier in front of every reading, so a phase's
+// time is that of its slowest wave) and leaves the item's seven sums and its tile count in trace[workgroup][8]
+#define BT(slot) do { __builtin_amdgcn_s_barrier(); if (tid == 0) { long long now = (long long)wall_clock64(); tacc[slot] += now - tlast; tlast = now; } } while (0)
+#else
+#define BT(slot) do {} while (0)
+#endif
 template <int NMT>
 __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item) {
     float* G = reinterpret_cast<float*>(smem);                   // [CH][GST]
@@ -219,6 +237,10 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 15, lg = lane >> 4;
     const int n = item.z;
+#ifdef CORR_TRACE
+    long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long tlast = (long long)wall_clock64();
+#endif
     int b, u, v;
     corr_cell_coords(a.g, item.x, &b, &u, &v);
     u += a.g.u_min; v += a.g.v_min;
@@ -232,6 +254,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
     }
     if (tid < TAB_PAD) rowoff[CH + tid] = BAD_OFF;
     __syncthreads();
+    BT(0);
     const __amdgpu_buffer_rsrc_t r_f1 = rsrc_of(a.f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
     const __amdgpu_buffer_rsrc_t r_d1 = rsrc_of(a.d_f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
 
@@ -244,6 +267,27 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
 #pragma unroll
             for (int nt = 0; nt < NTW; ++nt) acc1[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+        // Tap gradients of one level, from d_out straight into LDS (no registers in between, so the loads can fly
+        // under a contraction): wave = (half of the queries, every fourth tap), lane = query.  The level's K*K
+        // planes of this batch item are one buffer: the lane's pixel is the vector offset (an empty slot's lies
+        // past the end and lands as zero), the tap's plane a scalar offset; a wave's 64 values land at
+        // taps[t][64 * half + lane].
+        const unsigned tq_off = (tid & (CORR_GROUP - 1)) < n ? q_off[tid & (CORR_GROUP - 1)] / (unsigned)D : BAD_OFF;   // pixel * 4
+        int tv_level = -1;
+        auto load_taps = [&](int lv) {
+            const uint64_t base = reinterpret_cast<uint64_t>(a.d_out + ((size_t)(b * a.L + lv) * KK) * a.HW);
+            i32x4 rs;
+            rs[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)base);
+            rs[1] = __builtin_amdgcn_readfirstlane((int)((base >> 32) & 0xffffu));
+            rs[2] = __builtin_amdgcn_readfirstlane(KK * a.HW * 4);
+            rs[3] = __builtin_amdgcn_readfirstlane(0x00020000);
+            const unsigned lds0 = __builtin_amdgcn_readfirstlane(
+                (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)taps + (unsigned)(wave & 1) * 256u);
+            for (int t = wave >> 1; t < KK; t += NTI / CORR_GROUP)
+                dma4(rs, __builtin_amdgcn_readfirstlane(lds0 + (unsigned)t * (CORR_GROUP * 4)), tq_off,
+                     __builtin_amdgcn_readfirstlane(t * a.HW * 4));
+            tv_level = lv;
+        };
         for (int l = 0; l < a.L; ++l) {
             const int Hl = a.Hl[l], Wl = a.Wl[l];
             const int CXL = max((1 << CORR_LOG_CX) >> l, 1), CYL = max((1 << CORR_LOG_CY) >> l, 1);
@@ -252,28 +296,14 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
             if (!(xs + WSX - 1 >= 0 && xs <= Wl - 1 && ys + WSY - 1 >= 0 && ys <= Hl - 1)) continue;   // all padding (uniform)
             const __amdgpu_buffer_rsrc_t r_f2 = rsrc_of(a.f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
             const __amdgpu_buffer_rsrc_t r_d2 = rsrc_of(a.d_f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
-            {
-                // this level's tap gradients: all loads of a thread in flight at once, then into LDS (the first
-                // pass's barriers order them before the reads; the barrier here, after the previous level's)
-                const int q = tid & (CORR_GROUP - 1), part = tid >> 7;
-                float tv[TAPS_PER_THREAD];
-                // the level's K*K planes of this batch item as one buffer: the lane's pixel is the vector offset,
-                // the tap's plane (the same for a whole wave) a scalar offset
-                const __amdgpu_buffer_rsrc_t r_do = rsrc_of(a.d_out + ((size_t)(b * a.L + l) * KK) * a.HW, (size_t)KK * a.HW);
-                const unsigned poff = q < n ? q_off[q] / (unsigned)D : BAD_OFF;      // pixel * 4
-                const int wpart = __builtin_amdgcn_readfirstlane(part);
-#pragma unroll
-                for (int i = 0; i < TAPS_PER_THREAD; ++i) {
-                    const int t = min(wpart + i * (NTI / CORR_GROUP), KK - 1);
-                    tv[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_do, (int)poff, t * a.HW * 4, 0));
-                }
+            // this level's tap gradients: on their way into LDS since the previous level's last pass, or loaded now
+            // (the first level, or one after a level that was all padding)
+            if (tv_level != l) {
                 __syncthreads();                                 // the previous level's last pass no longer reads taps
-#pragma unroll
-                for (int i = 0; i < TAPS_PER_THREAD; ++i) {
-                    const int t = part + i * (NTI / CORR_GROUP);
-                    if (t < KK) taps[t * CORR_GROUP + q] = tv[i];
-                }
+                load_taps(l);
             }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's part has landed; the passes' barriers cover the others'
+            BT(1);
             for (int r0 = 0; r0 < NPTS; r0 += CH) {
                 __syncthreads();                                 // the previous pass no longer reads G or rowoff
                 {
@@ -286,6 +316,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                     }
                 }
                 __syncthreads();
+                BT(2);
                 {
                     // footprint weights into G: thread = (query, quarter of the footprint columns).  Point (pu, pv)
                     // collects the taps (pu - du, pv - dv), du, dv in {0, 1}, with their corner weights; every
@@ -302,22 +333,29 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                         const float* dp = taps + q;
                         float* gq = G + q;
                         for (int pu = p0; pu < p1; ++pu) {
-                            float tprev = 0.f;
+                            // the column's horizontally weighted taps first (all LDS reads in flight at once), then its K + 1 points
+                            const float w0 = pu < K ? wx0 : 0.f, w1 = pu >= 1 ? wx1 : 0.f;
+                            const float* c0 = dp + min(pu, K - 1) * K * CORR_GROUP;
+                            const float* c1 = dp + max(pu - 1, 0) * K * CORR_GROUP;
+                            float t[MAXK + 1];
+#pragma unroll
+                            for (int j = 0; j < MAXK; ++j) {
+                                const int jj = min(j, K - 1);
+                                t[j] = j < K ? c0[jj * CORR_GROUP] * w0 + c1[jj * CORR_GROUP] * w1 : 0.f;
+                            }
+                            t[MAXK] = 0.f;
                             int rr = ry * WSX + rx + pu - r0;
-                            for (int pv = 0; pv <= K; ++pv) {
-                                float t = 0.f;
-                                if (pv < K) {
-                                    if (pu < K) t = dp[(pu * K + pv) * CORR_GROUP] * wx0;
-                                    if (pu >= 1) t += dp[((pu - 1) * K + pv) * CORR_GROUP] * wx1;
-                                }
-                                if ((unsigned)rr < (unsigned)CH) gq[rr * GST] = t + fy * (tprev - t);
-                                tprev = t;
+#pragma unroll
+                            for (int pv = 0; pv <= MAXK; ++pv) {
+                                const float tprev = pv >= 1 ? t[pv - 1] : 0.f;
+                                if (pv <= K && (unsigned)rr < (unsigned)CH) gq[rr * GST] = t[pv] + fy * (tprev - t[pv]);
                                 rr += WSX;
                             }
                         }
                     }
                 }
                 __syncthreads();
+                BT(3);
                 if (wave_on) {
                     const int rows = min(CH, NPTS - r0);
                     const unsigned ch4 = (unsigned)ch * 4u;
@@ -358,6 +396,14 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                             }
                         }
                     }
+                }
+                BT(4);
+                // the next level's tap gradients start to move under the second contraction of this level's last
+                // pass (every wave is past the pass's scatter, the last reader of the current ones)
+                if (r0 + CH >= NPTS && l + 1 < a.L) load_taps(l + 1);
+                if (wave_on) {
+                    const int rows = min(CH, NPTS - r0);
+                    const unsigned ch4 = (unsigned)ch * 4u;
                     // d f2_l rows of this pass = G x f1, over as many 16-point tiles as the pass has rows (rounded up to odd)
                     const int tiles = (rows + 15) >> 4;
                     if (tiles <= 3) rows_gradient<NMT, 3>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
@@ -365,6 +411,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                     else if (tiles <= 7) rows_gradient<NMT, 7>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
                     else rows_gradient<NMT, MTC>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
                 }
+                BT(5);
             }
         }
         if (wave_on) {
@@ -379,6 +426,10 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                 }
         }
     }
+#ifdef CORR_TRACE
+    BT(6);
+    if (tid == 0 && a.trace) { for (int i = 0; i < 7; ++i) a.trace[(size_t)blockIdx.x * 8 + i] = tacc[i]; a.trace[(size_t)blockIdx.x * 8 + 7] = NMT; }
+#endif
 }
 
 __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
@@ -460,6 +511,10 @@ size_t corr_backward_workspace_bytes_internal(int B, int H, int W, int D, int L)
     return grad_bytes(B, H, W, D, L) + corr_ws_layout(B * H * W, corr_ncells(g, B)).total;
 }
 
+#ifdef CORR_TRACE
+static long long* g_bwd_trace = nullptr;
+extern "C" void corr_debug_set_backward_trace(long long* p) { g_bwd_trace = p; }
+#endif
 hipError_t launch_backward(const corr_pyramid* p, const float* coords, const float* d_out, int r,
                            float* d_fmap1, float* d_fmap2, float* ws, int form, hipStream_t s) {
     const int HW = p->H * p->W;
@@ -489,6 +544,9 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, ITEM_LDS);
         if (attr != hipSuccess) return attr;
         BwdItemArgs a;
+#ifdef CORR_TRACE
+        a.trace = g_bwd_trace;
+#endif
         a.f1 = p->f1_nhwc; a.d_f1 = d_f1; a.d_out = d_out;
         a.perm = bws.perm; a.sorted_c = bws.sorted_c; a.items = bws.items; a.n_items = bws.n_items;
         a.B = p->B; a.HW = HW; a.D = p->D; a.L = p->L; a.r = r; a.g = p->grid; a.scale = scale;

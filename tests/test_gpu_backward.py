@@ -21,8 +21,23 @@ CASES = [
     (2, 16, 24, 32, 4, 4, 12.0),      # batch, D smaller than a wave
     (1, 8, 8, 96, 4, 4, 3.0),         # level 3 is a single pixel; D not a multiple of 64
     (1, 19, 27, 160, 2, 2, 30.0),     # r = 2, many windows outside
-    (1, 13, 17, 320, 4, 1, 5.0),      # r = 1, five channel slots per lane
+    (1, 13, 17, 320, 4, 1, 5.0),      # r = 1, five channel slots per lane; a second, partly filled channel group
+    (2, 40, 60, 64, 4, 4, 9.0),       # 4800 queries: the count + scatter binning path, items of every fill
+    (1, 12, 20, 512, 3, 3, 4.0),      # r = 3, two full channel groups
 ]
+FORMS = ["items", "queries"]
+
+
+@pytest.fixture(params=FORMS)
+def form(request):
+    """Every oracle comparison runs for both kernels behind the entry point: the work-item form on the matrix
+    cores (the default) and the one-wave-per-query form."""
+    from paper_2505_16942_amd import binding
+    binding.load_library()
+    prev = binding.corr_debug_set_backward_form(
+        binding.CORR_BACKWARD_ITEMS if request.param == "items" else binding.CORR_BACKWARD_QUERIES)
+    yield request.param
+    binding.corr_debug_set_backward_form(prev)
 
 
 def _binding():
@@ -41,9 +56,9 @@ def _check(got, want, what):
 
 
 @pytest.mark.parametrize("case", CASES)
-def test_gradients_match_the_oracle(case):
+def test_gradients_match_the_oracle(case, form):
     B, H, W, D, L, r, fr = case
-    print("case", case, flush=True)
+    print("case", case, "form", form, flush=True)
     b = _binding()
     dev = torch.device("cuda:0")
     f1, f2, c = synth.small_case(300 + H, B, H, W, D, flow_range=fr)
@@ -65,7 +80,7 @@ def test_gradients_match_the_oracle(case):
     # a second call on the same workspace (now holding the first call's leftovers) gives the same result to rounding
     h1, h2 = b.corr_sample_backward(pyr, tc, tg, r=r, workspace=ws)
     torch.cuda.synchronize()
-    assert torch.equal(h1, g1)                          # no atomics on this output: same bits
+    assert torch.equal(h1, g1)                          # no atomics on this output, one writer per partial sum: same bits
     _check(h2, want2, "d_fmap2, second call %s" % (case,))
     pyr.destroy()
 
@@ -95,6 +110,55 @@ def test_backward_agrees_with_the_forward_kernel_by_the_adjoint_identity():
     assert abs(lhs1 - rhs1) <= scale and abs(lhs2 - rhs2) <= scale
     for p in (pyr, pa, pb):
         p.destroy()
+
+
+def test_the_two_forms_agree_at_1080p():
+    """The work-item form against the one-wave-per-query form at a size with many full items (135 x 240, D = 256,
+    ~330 items): both sum the same fp32 products in different orders, so they agree to a few 1e-6 of the largest
+    gradient; and the work-item form's d_fmap1 is the same bits on a second call."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    cfg = synth.config("1080p")
+    f1, f2 = synth.features(cfg)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, synth.coords(cfg)))
+    gen = torch.Generator(device=dev); gen.manual_seed(9)
+    d_out = torch.randn((1, 324, 135, 240), device=dev, generator=gen)
+    pyr = b.corr_pyramid_build(t1, t2, L=4, reps=b.CORR_REP_F32)
+    res = {}
+    try:
+        for name, form_id in (("items", b.CORR_BACKWARD_ITEMS), ("queries", b.CORR_BACKWARD_QUERIES)):
+            b.corr_debug_set_backward_form(form_id)
+            res[name] = b.corr_sample_backward(pyr, tc, d_out)
+        b.corr_debug_set_backward_form(b.CORR_BACKWARD_ITEMS)
+        again = b.corr_sample_backward(pyr, tc, d_out)
+    finally:
+        b.corr_debug_set_backward_form(b.CORR_BACKWARD_ITEMS)
+    torch.cuda.synchronize()
+    for i, what in enumerate(("d_fmap1", "d_fmap2")):
+        m = float(res["queries"][i].abs().max())
+        err = float((res["items"][i] - res["queries"][i]).abs().max())
+        print("%s: max|items - queries| = %.3e, max|grad| = %.3f" % (what, err, m), flush=True)
+        assert err <= 1e-5 * m
+    assert torch.equal(again[0], res["items"][0])
+    pyr.destroy()
+
+
+def test_backward_leaves_the_pyramids_plan_alone():
+    """The gradient bins the queries in its own workspace: a lookup's plan in the pyramid (read back through the
+    test hook) is the same before and after a backward call with other coordinates."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    f1, f2, c = synth.small_case(77, 1, 40, 56, 64, flow_range=6.0)
+    t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, c))
+    pyr = b.corr_pyramid_build(t1, t2, L=4, reps=b.CORR_REP_F32 | b.CORR_REP_SPLIT)
+    b.corr_sample(t1, pyr, tc)
+    items0, perm0 = b.corr_debug_read_plan(pyr)
+    other = torch.from_numpy(synth.small_case(78, 1, 40, 56, 64, flow_range=15.0)[2]).to(dev)
+    b.corr_sample_backward(pyr, other, torch.ones((1, 324, 40, 56), device=dev))
+    torch.cuda.synchronize()
+    items1, perm1 = b.corr_debug_read_plan(pyr)
+    assert np.array_equal(items0, items1) and np.array_equal(perm0, perm1)
+    pyr.destroy()
 
 
 def test_backward_error_paths():
