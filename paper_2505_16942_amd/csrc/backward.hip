@@ -9,10 +9,12 @@
 //     d f2_l(q)     += G[v][u] / sqrt(D) * f1(p)          (q = origin + (u, v), inside the level)
 // and the levels' gradients go down the pyramid by the adjoint of the 2x2 mean.
 //
-// This is the on-demand form: one wave per query, fp32 vector ALU, channels across lanes, hardware float
-// atomics for d f2_l (its footprints overlap between queries).  fp32 channels-last representation of the
-// pyramid (CORR_REP_F32), gradients accumulated channels-last in a caller-provided workspace and transposed
-// to NCHW at the end.  Summation order of the atomics is not fixed: results agree to rounding, not bit for bit.
+// Both forms below read the fp32 channels-last representation of the pyramid (CORR_REP_F32), accumulate the
+// gradients channels-last in a caller-provided workspace and bring them to NCHW at the end.  Summation order of
+// the atomics on d f2_l is not fixed: d_fmap2 agrees between calls to rounding, not bit for bit.
+//
+// The first form is the plain one: one wave per query, fp32 vector ALU, channels across lanes, a hardware float
+// atomic per (footprint point, channel) for d f2_l.  The second, further down, is what the entry point runs.
 #include "corr_internal.h"
 
 namespace {
@@ -225,7 +227,8 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
 #else
 #define BT(slot) do {} while (0)
 #endif
-template <int NMT>
+// KT: the window side 2r + 1 as a constant (the largest radius, the usual one), or 0: taken from the arguments
+template <int NMT, int KT>
 __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item) {
     float* G = reinterpret_cast<float*>(smem);                   // [CH][GST]
     // byte offset of the feature row (pixel * D * 4) of each point of the pass / of each query slot; BAD_OFF: outside the level / empty
@@ -244,7 +247,8 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
     int b, u, v;
     corr_cell_coords(a.g, item.x, &b, &u, &v);
     u += a.g.u_min; v += a.g.v_min;
-    const int K = 2 * a.r + 1, KK = K * K, D = a.D;
+    const int K = KT ? KT : 2 * a.r + 1, KK = K * K, D = a.D;
+    const int R = (K - 1) / 2;
     if (tid < CORR_GROUP + TAB_PAD) {
         int pix = -1;
         float2 xy = make_float2(0.f, 0.f);
@@ -292,7 +296,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
             const int Hl = a.Hl[l], Wl = a.Wl[l];
             const int CXL = max((1 << CORR_LOG_CX) >> l, 1), CYL = max((1 << CORR_LOG_CY) >> l, 1);
             const int WSX = CXL + K, WSY = CYL + K, NPTS = WSX * WSY;
-            const int xs = ((u << CORR_LOG_CX) >> l) - a.r, ys = ((v << CORR_LOG_CY) >> l) - a.r;
+            const int xs = ((u << CORR_LOG_CX) >> l) - R, ys = ((v << CORR_LOG_CY) >> l) - R;
             if (!(xs + WSX - 1 >= 0 && xs <= Wl - 1 && ys + WSY - 1 >= 0 && ys <= Hl - 1)) continue;   // all padding (uniform)
             const __amdgpu_buffer_rsrc_t r_f2 = rsrc_of(a.f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
             const __amdgpu_buffer_rsrc_t r_d2 = rsrc_of(a.d_f2[l] + (size_t)b * Hl * Wl * D, (size_t)Hl * Wl * D);
@@ -327,7 +331,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                         const float cxl = q_cx[q] * inv, cyl = q_cy[q] * inv;
                         const float flx = floorf(cxl), fly = floorf(cyl);
                         const float fx = cxl - flx, fy = cyl - fly;
-                        const int rx = (int)flx - a.r - xs, ry = (int)fly - a.r - ys;
+                        const int rx = (int)flx - R - xs, ry = (int)fly - R - ys;
                         const float wx1 = fx * a.scale, wx0 = a.scale - wx1;
                         const int p0 = part * (K + 1) / 4, p1 = (part + 1) * (K + 1) / 4;
                         const float* dp = taps + q;
@@ -426,6 +430,8 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                 }
         }
     }
+    // a prefetch for a level that turned out to be all padding may still be in flight: nothing may land in LDS after the end
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #ifdef CORR_TRACE
     BT(6);
     if (tid == 0 && a.trace) { for (int i = 0; i < 7; ++i) a.trace[(size_t)blockIdx.x * 8 + i] = tacc[i]; a.trace[(size_t)blockIdx.x * 8 + 7] = NMT; }
@@ -437,15 +443,29 @@ __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
     const int k = corr_item_of_workgroup(blockIdx.x);
     if (k >= *a.n_items) return;
     const int4 item = a.items[k];
-    switch ((item.z + 15) >> 4) {                          // uniform
-        case 1: bwd_item_body<1>(a, smem, item); break;
-        case 2: bwd_item_body<2>(a, smem, item); break;
-        case 3: bwd_item_body<3>(a, smem, item); break;
-        case 4: bwd_item_body<4>(a, smem, item); break;
-        case 5: bwd_item_body<5>(a, smem, item); break;
-        case 6: bwd_item_body<6>(a, smem, item); break;
-        case 7: bwd_item_body<7>(a, smem, item); break;
-        default: bwd_item_body<8>(a, smem, item); break;
+    const int tiles = (item.z + 15) >> 4;                  // uniform
+    if (a.r == CORR_R) {
+        switch (tiles) {
+            case 1: bwd_item_body<1, MAXK>(a, smem, item); break;
+            case 2: bwd_item_body<2, MAXK>(a, smem, item); break;
+            case 3: bwd_item_body<3, MAXK>(a, smem, item); break;
+            case 4: bwd_item_body<4, MAXK>(a, smem, item); break;
+            case 5: bwd_item_body<5, MAXK>(a, smem, item); break;
+            case 6: bwd_item_body<6, MAXK>(a, smem, item); break;
+            case 7: bwd_item_body<7, MAXK>(a, smem, item); break;
+            default: bwd_item_body<8, MAXK>(a, smem, item); break;
+        }
+    } else {
+        switch (tiles) {
+            case 1: bwd_item_body<1, 0>(a, smem, item); break;
+            case 2: bwd_item_body<2, 0>(a, smem, item); break;
+            case 3: bwd_item_body<3, 0>(a, smem, item); break;
+            case 4: bwd_item_body<4, 0>(a, smem, item); break;
+            case 5: bwd_item_body<5, 0>(a, smem, item); break;
+            case 6: bwd_item_body<6, 0>(a, smem, item); break;
+            case 7: bwd_item_body<7, 0>(a, smem, item); break;
+            default: bwd_item_body<8, 0>(a, smem, item); break;
+        }
     }
 }
 

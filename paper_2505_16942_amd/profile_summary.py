@@ -81,7 +81,7 @@ def cmd_stats(args) -> int:
     print("| kernel | grid (threads) | calls | mean us | min us | max us | total ms | share |")
     print("|---|---|---|---|---|---|---|---|")
     for (name, grid), v in sorted(rows.items(), key=lambda kv: -sum(kv[1])):
-        if sum(v) / total < 0.002 and "corr" not in name and "block" not in name and "bin" not in name:
+        if sum(v) / total < 0.002 and not any(w in name for w in ("corr", "block", "bin", "bwd", "fill_i32")):
             continue
         print("| %s | %d | %d | %.1f | %.1f | %.1f | %.3f | %.1f %% |" % (
             _short(name), grid, len(v), sum(v) / len(v), min(v), max(v), sum(v) / 1e3, 100.0 * sum(v) / total))
@@ -134,7 +134,7 @@ def cmd_counters(args) -> int:
     print("|---|---|---|---|")
     for d in args.dirs:
         for k, v in _counter_rows(d).items():
-            if not any(w in k for w in ("block_kernel", "bin_", "build_features", "copy_f32")):
+            if not any(w in k for w in ("block_kernel", "bin_", "build_features", "copy_f32", "bwd_")):
                 continue
             for cname, vals in sorted(v.items()):
                 print("| %s | %s | %d | %.6g |" % (_short(k), cname, len(vals), sum(vals) / len(vals)))
