@@ -469,47 +469,49 @@ __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
     }
 }
 
-// [B][HW][D] -> [B][D][HW] through a 32 x 32 LDS tile
-__global__ __launch_bounds__(256) void bwd_to_nchw_kernel(const float* __restrict__ src, float* __restrict__ dst, int HW, int D) {
-    __shared__ float tile[32][33];
-    const int b = blockIdx.z, p0 = blockIdx.x * 32, d0 = blockIdx.y * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
-    for (int r = ty; r < 32; r += 8)
-        if (p0 + r < HW && d0 + tx < D) tile[r][tx] = src[((size_t)b * HW + p0 + r) * D + d0 + tx];
-    __syncthreads();
-    for (int r = ty; r < 32; r += 8)
-        if (d0 + r < D && p0 + tx < HW) dst[((size_t)b * D + d0 + r) * HW + p0 + tx] = tile[tx][r];
-}
-
-// d_fmap2 from the levels' gradients, channels-last to NCHW in the same pass.  Adjoint of the 2x2 mean: a pixel of
-// level l - 1 receives a quarter of its parent's gradient at level l, if it has a parent (a trailing odd row or
-// column that the pooling dropped has none, and then none at the deeper levels either).  For a level-0 pixel that
-// is the nested sum d0 + (d1 + (d2 + d3 / 4) / 4) / 4 along its chain of parents, evaluated from the deepest level.
+// Channels-last gradients to NCHW, and for fmap2 the levels' gradients down the pyramid in the same pass.
+// Adjoint of the 2x2 mean: a pixel of level l - 1 receives a quarter of its parent's gradient at level l, if it
+// has a parent (a trailing odd row or column that the pooling dropped has none, and then none at the deeper
+// levels either).  For a level-0 pixel that is the nested sum d0 + (d1 + (d2 + d3 / 4) / 4) / 4 along its chain
+// of parents, evaluated from the deepest level.  With L = 1 this is a plain transposition (d_fmap1).
+// A workgroup moves 64 pixels x 64 channels through LDS: 16-byte loads along the channels (a wave reads four
+// pixels' 256 bytes), 256-byte runs along the pixels on the way out.
 struct GatherArgs {
     const float* d[CORR_MAX_L];
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     int L, D, W, HW;
 };
+constexpr int TP = 64, TC = 64;
 __global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, float* __restrict__ dst) {
-    __shared__ float tile[32][33];
-    const int b = blockIdx.z, p0 = blockIdx.x * 32, d0 = blockIdx.y * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    for (int r = ty; r < 32; r += 8) {
-        const int p = p0 + r, ch = d0 + tx;
-        if (p < g.HW && ch < g.D) {
+    __shared__ float tile[TC][TP + 1];
+    const int b = blockIdx.z, p0 = blockIdx.x * TP, d0 = blockIdx.y * TC;
+#pragma unroll
+    for (int k = 0; k < TP * TC / 4 / 256; ++k) {
+        const int idx = threadIdx.x + 256 * k, c4 = idx & (TC / 4 - 1), pr = idx / (TC / 4);
+        const int p = p0 + pr, ch = d0 + 4 * c4;
+        if (p < g.HW && ch < g.D) {                        // D is a multiple of 4
             const int y = p / g.W, x = p - y * g.W;
-            float t = 0.f;
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int l = g.L - 1; l >= 1; --l) {
                 const int yy = y >> l, xx = x >> l;
-                if (yy < g.Hl[l] && xx < g.Wl[l])
-                    t = g.d[l][(((size_t)b * g.Hl[l] + yy) * g.Wl[l] + xx) * g.D + ch] + 0.25f * t;
+                if (yy < g.Hl[l] && xx < g.Wl[l]) {
+                    const float4 v = *reinterpret_cast<const float4*>(g.d[l] + (((size_t)b * g.Hl[l] + yy) * g.Wl[l] + xx) * g.D + ch);
+                    t = make_float4(v.x + 0.25f * t.x, v.y + 0.25f * t.y, v.z + 0.25f * t.z, v.w + 0.25f * t.w);
+                }
             }
-            tile[r][tx] = g.d[0][((size_t)b * g.HW + p) * g.D + ch] + 0.25f * t;
+            const float4 v = *reinterpret_cast<const float4*>(g.d[0] + ((size_t)b * g.HW + p) * g.D + ch);
+            tile[4 * c4 + 0][pr] = v.x + 0.25f * t.x;
+            tile[4 * c4 + 1][pr] = v.y + 0.25f * t.y;
+            tile[4 * c4 + 2][pr] = v.z + 0.25f * t.z;
+            tile[4 * c4 + 3][pr] = v.w + 0.25f * t.w;
         }
     }
     __syncthreads();
-    for (int r = ty; r < 32; r += 8)
-        if (d0 + r < g.D && p0 + tx < g.HW) dst[((size_t)b * g.D + d0 + r) * g.HW + p0 + tx] = tile[tx][r];
+#pragma unroll
+    for (int k = 0; k < TP * TC / 256; ++k) {
+        const int idx = threadIdx.x + 256 * k, px = idx & (TP - 1), chn = idx / TP;
+        if (d0 + chn < g.D && p0 + px < g.HW) dst[((size_t)b * g.D + d0 + chn) * g.HW + p0 + px] = tile[chn][px];
+    }
 }
 
 }  // namespace
@@ -589,12 +591,14 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
         hipLaunchKernelGGL(bwd_query_kernel, dim3((unsigned)((BN + BQ - 1) / BQ)), dim3(64 * BQ), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    dim3 tg((HW + 31) / 32, (p->D + 31) / 32, p->B);
-    hipLaunchKernelGGL(bwd_to_nchw_kernel, tg, dim3(256), 0, s, d_f1, d_fmap1, HW, p->D);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    dim3 tg((HW + TP - 1) / TP, (p->D + TC - 1) / TC, p->B);
     GatherArgs ga;
-    for (int l = 0; l < CORR_MAX_L; ++l) { ga.d[l] = d_f2[l]; ga.Hl[l] = p->Hl[l]; ga.Wl[l] = p->Wl[l]; }
-    ga.L = p->L; ga.D = p->D; ga.W = p->W; ga.HW = HW;
+    for (int l = 0; l < CORR_MAX_L; ++l) { ga.d[l] = nullptr; ga.Hl[l] = p->Hl[l]; ga.Wl[l] = p->Wl[l]; }
+    ga.d[0] = d_f1; ga.L = 1; ga.D = p->D; ga.W = p->W; ga.HW = HW;
+    hipLaunchKernelGGL(bwd_gather_nchw_kernel, tg, dim3(256), 0, s, ga, d_fmap1);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    for (int l = 0; l < CORR_MAX_L; ++l) ga.d[l] = d_f2[l];
+    ga.L = p->L;
     hipLaunchKernelGGL(bwd_gather_nchw_kernel, tg, dim3(256), 0, s, ga, d_fmap2);
     return hipGetLastError();
 }
