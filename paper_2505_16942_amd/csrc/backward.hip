@@ -139,6 +139,7 @@ struct BwdItemArgs {
     const float2* sorted_c;
     const int4* items;
     const int* n_items;
+    int* queue;                             // [8] next queue position per XCD, zero on entry
     int B, HW, D, L, r;
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     CellGrid g;
@@ -229,7 +230,7 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
 #endif
 // KT: the window side 2r + 1 as a constant (the largest radius, the usual one), or 0: taken from the arguments
 template <int NMT, int KT>
-__device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item) {
+__device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item, const int k) {
     float* G = reinterpret_cast<float*>(smem);                   // [CH][GST]
     // byte offset of the feature row (pixel * D * 4) of each point of the pass / of each query slot; BAD_OFF: outside the level / empty
     unsigned* rowoff = reinterpret_cast<unsigned*>(smem + CH * GST * 4);   // [CH + pad]
@@ -434,37 +435,62 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #ifdef CORR_TRACE
     BT(6);
-    if (tid == 0 && a.trace) { for (int i = 0; i < 7; ++i) a.trace[(size_t)blockIdx.x * 8 + i] = tacc[i]; a.trace[(size_t)blockIdx.x * 8 + 7] = NMT; }
+    if (tid == 0 && a.trace) { for (int i = 0; i < 7; ++i) a.trace[(size_t)k * 8 + i] = tacc[i]; a.trace[(size_t)k * 8 + 7] = NMT; }
 #endif
 }
 
+// One workgroup per compute unit, each taking items from a queue until it is empty.  Workgroup w runs on XCD
+// w % 8 and serves that XCD's share of the item list (runs of CORR_XCD_RUN consecutive items, as in the forward
+// kernel: neighbouring cells share window rows, so they should share an L2).  A queue goes over its share three
+// times and each time hands out one class of items: the full ones, the middle ones, the small ones (a workgroup
+// whose queue has run out goes on with the next XCD's).  The long
+// items so start first and the short ones fill the end of the launch, and no compute unit spends time on
+// workgroups that find nothing to do (one of this kernel's workgroups needs most of a unit's LDS, so even an
+// empty one waits for a unit of its own).
 __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int k = corr_item_of_workgroup(blockIdx.x);
-    if (k >= *a.n_items) return;
-    const int4 item = a.items[k];
-    const int tiles = (item.z + 15) >> 4;                  // uniform
-    if (a.r == CORR_R) {
-        switch (tiles) {
-            case 1: bwd_item_body<1, MAXK>(a, smem, item); break;
-            case 2: bwd_item_body<2, MAXK>(a, smem, item); break;
-            case 3: bwd_item_body<3, MAXK>(a, smem, item); break;
-            case 4: bwd_item_body<4, MAXK>(a, smem, item); break;
-            case 5: bwd_item_body<5, MAXK>(a, smem, item); break;
-            case 6: bwd_item_body<6, MAXK>(a, smem, item); break;
-            case 7: bwd_item_body<7, MAXK>(a, smem, item); break;
-            default: bwd_item_body<8, MAXK>(a, smem, item); break;
+    __shared__ int s_next;
+    int xcd = (int)blockIdx.x & 7, tried = 0;
+    const int n_items = *a.n_items;
+    const int share = (n_items + 8 * CORR_XCD_RUN - 1) / (8 * CORR_XCD_RUN) * CORR_XCD_RUN;   // queue positions per round
+    for (;;) {
+        __syncthreads();                                   // the previous item's last LDS reads; s_next has been read
+        if (threadIdx.x == 0) s_next = atomicAdd(a.queue + xcd, 1);
+        __syncthreads();
+        const int pos = s_next;                            // uniform
+        if (pos >= 3 * share) {                            // this queue is empty: help the next XCD's, until all eight are
+            if (++tried == 8) break;
+            xcd = (xcd + 1) & 7;
+            continue;
         }
-    } else {
-        switch (tiles) {
-            case 1: bwd_item_body<1, 0>(a, smem, item); break;
-            case 2: bwd_item_body<2, 0>(a, smem, item); break;
-            case 3: bwd_item_body<3, 0>(a, smem, item); break;
-            case 4: bwd_item_body<4, 0>(a, smem, item); break;
-            case 5: bwd_item_body<5, 0>(a, smem, item); break;
-            case 6: bwd_item_body<6, 0>(a, smem, item); break;
-            case 7: bwd_item_body<7, 0>(a, smem, item); break;
-            default: bwd_item_body<8, 0>(a, smem, item); break;
+        const int round = pos / share;
+        const int k = corr_item_of_workgroup((pos - round * share) * 8 + xcd);
+        if (k >= n_items) continue;
+        const int4 item = a.items[k];
+        const int tiles = (item.z + 15) >> 4;
+        if ((tiles == 8 ? 0 : tiles >= 5 ? 1 : 2) != round) continue;
+        if (a.r == CORR_R) {
+            switch (tiles) {
+                case 1: bwd_item_body<1, MAXK>(a, smem, item, k); break;
+                case 2: bwd_item_body<2, MAXK>(a, smem, item, k); break;
+                case 3: bwd_item_body<3, MAXK>(a, smem, item, k); break;
+                case 4: bwd_item_body<4, MAXK>(a, smem, item, k); break;
+                case 5: bwd_item_body<5, MAXK>(a, smem, item, k); break;
+                case 6: bwd_item_body<6, MAXK>(a, smem, item, k); break;
+                case 7: bwd_item_body<7, MAXK>(a, smem, item, k); break;
+                default: bwd_item_body<8, MAXK>(a, smem, item, k); break;
+            }
+        } else {
+            switch (tiles) {
+                case 1: bwd_item_body<1, 0>(a, smem, item, k); break;
+                case 2: bwd_item_body<2, 0>(a, smem, item, k); break;
+                case 3: bwd_item_body<3, 0>(a, smem, item, k); break;
+                case 4: bwd_item_body<4, 0>(a, smem, item, k); break;
+                case 5: bwd_item_body<5, 0>(a, smem, item, k); break;
+                case 6: bwd_item_body<6, 0>(a, smem, item, k); break;
+                case 7: bwd_item_body<7, 0>(a, smem, item, k); break;
+                default: bwd_item_body<8, 0>(a, smem, item, k); break;
+            }
         }
     }
 }
@@ -560,6 +586,7 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
         // the bin and item counters start at zero; everything else in the planning workspace is written before it is read
         if ((e = launch_fill_i32(bws.bin_count, 0, (size_t)bws.nbins, s)) != hipSuccess) return e;
         if ((e = launch_fill_i32(bws.n_items, 0, CORR_NCOUNTERS, s)) != hipSuccess) return e;
+        if ((e = launch_fill_i32(reinterpret_cast<int*>(bws.stats), 0, 8, s)) != hipSuccess) return e;   // the item kernel's queues
         LookupArgs q{coords, nullptr, r, 0, 0, 0};
         if ((e = launch_binning(p, bws, q, s)) != hipSuccess) return e;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_item_kernel),
@@ -570,13 +597,13 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
         a.trace = g_bwd_trace;
 #endif
         a.f1 = p->f1_nhwc; a.d_f1 = d_f1; a.d_out = d_out;
-        a.perm = bws.perm; a.sorted_c = bws.sorted_c; a.items = bws.items; a.n_items = bws.n_items;
+        a.perm = bws.perm; a.sorted_c = bws.sorted_c; a.items = bws.items; a.n_items = bws.n_items; a.queue = reinterpret_cast<int*>(bws.stats);
         a.B = p->B; a.HW = HW; a.D = p->D; a.L = p->L; a.r = r; a.g = p->grid; a.scale = scale;
         for (int l = 0; l < CORR_MAX_L; ++l) {
             a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr; a.d_f2[l] = d_f2[l];
             a.Hl[l] = p->Hl[l]; a.Wl[l] = p->Wl[l];
         }
-        hipLaunchKernelGGL(bwd_item_kernel, dim3(corr_block_grid(bws.max_items)), dim3(NTI), ITEM_LDS, s, a);
+        hipLaunchKernelGGL(bwd_item_kernel, dim3(CORR_NUM_CU), dim3(NTI), ITEM_LDS, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     } else {
         BwdArgs a;
