@@ -112,33 +112,37 @@ def test_backward_agrees_with_the_forward_kernel_by_the_adjoint_identity():
         p.destroy()
 
 
-def test_the_two_forms_agree_at_1080p():
-    """The work-item form against the one-wave-per-query form at a size with many full items (135 x 240, D = 256,
-    ~330 items): both sum the same fp32 products in different orders, so they agree to a few 1e-6 of the largest
-    gradient; and the work-item form's d_fmap1 is the same bits on a second call."""
+@pytest.mark.parametrize("cfg_name,r", [("1080p", 4), ("1080p", 2), ("voronoi", 4), ("voronoi", 3)])
+def test_the_two_forms_agree_at_benchmark_sizes(cfg_name, r):
+    """The work-item form against the one-wave-per-query form at sizes with hundreds of items of every fill
+    (135 x 240 and the batched 2 x 104 x 208 configuration, D = 256), at the largest radius and a smaller one:
+    both sum the same fp32 products in different orders, so they agree to a few 1e-6 of the largest gradient;
+    and the work-item form's d_fmap1 is the same bits on a second call."""
     b = _binding()
     dev = torch.device("cuda:0")
-    cfg = synth.config("1080p")
+    cfg = synth.config(cfg_name)
+    B, H, W, L = cfg["B"], cfg["H"], cfg["W"], cfg["L"]
+    K = 2 * r + 1
     f1, f2 = synth.features(cfg)
     t1, t2, tc = (torch.from_numpy(a).to(dev) for a in (f1, f2, synth.coords(cfg)))
     gen = torch.Generator(device=dev); gen.manual_seed(9)
-    d_out = torch.randn((1, 324, 135, 240), device=dev, generator=gen)
-    pyr = b.corr_pyramid_build(t1, t2, L=4, reps=b.CORR_REP_F32)
+    d_out = torch.randn((B, L * K * K, H, W), device=dev, generator=gen)
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_F32)
     res = {}
     try:
         for name, form_id in (("items", b.CORR_BACKWARD_ITEMS), ("queries", b.CORR_BACKWARD_QUERIES)):
             b.corr_debug_set_backward_form(form_id)
-            res[name] = b.corr_sample_backward(pyr, tc, d_out)
+            res[name] = b.corr_sample_backward(pyr, tc, d_out, r=r)
         b.corr_debug_set_backward_form(b.CORR_BACKWARD_ITEMS)
-        again = b.corr_sample_backward(pyr, tc, d_out)
+        again = b.corr_sample_backward(pyr, tc, d_out, r=r)
     finally:
         b.corr_debug_set_backward_form(b.CORR_BACKWARD_ITEMS)
     torch.cuda.synchronize()
     for i, what in enumerate(("d_fmap1", "d_fmap2")):
         m = float(res["queries"][i].abs().max())
         err = float((res["items"][i] - res["queries"][i]).abs().max())
-        print("%s: max|items - queries| = %.3e, max|grad| = %.3f" % (what, err, m), flush=True)
-        assert err <= 1e-5 * m
+        print("%s r=%d %s: max|items - queries| = %.3e, max|grad| = %.3f" % (cfg_name, r, what, err, m), flush=True)
+        assert m > 0 and err <= 1e-5 * m
     assert torch.equal(again[0], res["items"][0])
     pyr.destroy()
 
