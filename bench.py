@@ -413,6 +413,29 @@ def main() -> int:
                            "value": B4 * H4 * W4 * L4 * K * K * 12 * args.steps / dt4, "unit": "lookups/s",
                            "ms_per_step": dt4 * 1e3 / args.steps, "steps": args.steps}
         p4.destroy()
+        # and the gradient of the lookup on the same 4k pair (its own line: bench.py --backward): a few calls
+        pg = cb.corr_pyramid_build(u1, u2, L=L4, reps=cb.CORR_REP_F32)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(c4["seed"])
+        d_out = torch.randn((B4, L4 * K * K, H4, W4), device=dev, generator=gen)
+        wsb = torch.empty(cb.corr_backward_workspace_bytes(B4, H4, W4, c4["D"], L4) // 4, device=dev)
+        q1, q2 = torch.empty_like(u1), torch.empty_like(u1)
+        for _ in range(2):
+            cb.corr_sample_backward(pg, ucs[0], d_out, r=r, d_fmap1=q1, d_fmap2=q2, workspace=wsb)
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        for _ in range(args.steps):
+            cb.corr_sample_backward(pg, ucs[0], d_out, r=r, d_fmap1=q1, d_fmap2=q2, workspace=wsb)
+        torch.cuda.synchronize()
+        dtb = (time.perf_counter() - tb) / args.steps
+        win = sum((max(16 >> l, 1) + K) * (max(8 >> l, 1) + K) for l in range(L4))
+        tfs = 4.0 * B4 * H4 * W4 * win * c4["D"] / dtb / 1e12
+        result["backward_at_4k"] = {"workload": "4k, one corr_sample_backward per step (fp32, work items on fp32 MFMA)",
+                                    "value": B4 * H4 * W4 * L4 * K * K / dtb, "unit": "tap gradients/s",
+                                    "ms_per_step": dtb * 1e3, "steps": args.steps,
+                                    "roofline": {"bound": "mfma", "achieved": round(tfs, 2), "peak": PEAK_FP32_MFMA_TFS,
+                                                 "unit": "TFLOP/s", "frac": round(tfs / PEAK_FP32_MFMA_TFS, 4)}}
+        pg.destroy()
     print(json.dumps(result))
     return 0
 
