@@ -138,7 +138,8 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
  *               on the same pyramid.
  * Enqueues kernels on `stream` and returns; allocates nothing.  The queries are binned into the forward
  * pass's work items (a target cell and up to 128 of its queries); per item and level both gradients are
- * fp32 matrix-core contractions over the item's window.  fp32 throughout.  d_fmap1 has the same bits on
+ * fp32 matrix-core contractions over the item's window (inputs of up to 32000 queries run an item's levels
+ * in workgroups of their own and sum their shares of d_fmap1 in level order).  fp32 throughout.  d_fmap1 has the same bits on
  * every call; d_fmap2 is accumulated with floating-point atomics, so two calls agree to rounding, not bit
  * for bit.  Limits beyond corr_sample's: H*W*D*4 and H*W*(2r+1)^2*4 below 2^31 (one batch item's map and
  * one level's planes of d_out are addressed with 31-bit byte offsets), else CORR_ERR_UNSUPPORTED.

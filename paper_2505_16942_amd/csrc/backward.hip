@@ -140,6 +140,8 @@ struct BwdItemArgs {
     const int4* items;
     const int* n_items;
     int* queue;                             // [8] next queue position per XCD, zero on entry
+    int parts;                              // 1, or L: small inputs run an item's levels in workgroups of their own, each with
+                                            // a d_f1 array of its own (part p at d_f1 + p * B*HW*D), summed in order at the end
     int B, HW, D, L, r;
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     CellGrid g;
@@ -230,7 +232,8 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
 #endif
 // KT: the window side 2r + 1 as a constant (the largest radius, the usual one), or 0: taken from the arguments
 template <int NMT, int KT>
-__device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item, const int k) {
+__device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item, const int k,
+                                              const int lv_lo, const int lv_hi, const int part) {
     float* G = reinterpret_cast<float*>(smem);                   // [CH][GST]
     // byte offset of the feature row (pixel * D * 4) of each point of the pass / of each query slot; BAD_OFF: outside the level / empty
     unsigned* rowoff = reinterpret_cast<unsigned*>(smem + CH * GST * 4);   // [CH + pad]
@@ -261,7 +264,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
     __syncthreads();
     BT(0);
     const __amdgpu_buffer_rsrc_t r_f1 = rsrc_of(a.f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
-    const __amdgpu_buffer_rsrc_t r_d1 = rsrc_of(a.d_f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
+    const __amdgpu_buffer_rsrc_t r_d1 = rsrc_of(a.d_f1 + ((size_t)part * a.B + b) * a.HW * D, (size_t)a.HW * D);
 
     for (int cg = 0; cg < D; cg += 256) {                        // channel groups of 256: 32 per wave
         const int ch = cg + wave * (16 * NTW) + lr;              // this lane's channel of tile nt: ch + 16 * nt
@@ -293,7 +296,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                      __builtin_amdgcn_readfirstlane(t * a.HW * 4));
             tv_level = lv;
         };
-        for (int l = 0; l < a.L; ++l) {
+        for (int l = lv_lo; l < lv_hi; ++l) {
             const int Hl = a.Hl[l], Wl = a.Wl[l];
             const int CXL = max((1 << CORR_LOG_CX) >> l, 1), CYL = max((1 << CORR_LOG_CY) >> l, 1);
             const int WSX = CXL + K, WSY = CYL + K, NPTS = WSX * WSY;
@@ -405,7 +408,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                 BT(4);
                 // the next level's tap gradients start to move under the second contraction of this level's last
                 // pass (every wave is past the pass's scatter, the last reader of the current ones)
-                if (r0 + CH >= NPTS && l + 1 < a.L) load_taps(l + 1);
+                if (r0 + CH >= NPTS && l + 1 < lv_hi) load_taps(l + 1);
                 if (wave_on) {
                     const int rows = min(CH, NPTS - r0);
                     const unsigned ch4 = (unsigned)ch * 4u;
@@ -458,38 +461,41 @@ __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
         if (threadIdx.x == 0) s_next = atomicAdd(a.queue + xcd, 1);
         __syncthreads();
         const int pos = s_next;                            // uniform
-        if (pos >= 3 * share) {                            // this queue is empty: help the next XCD's, until all eight are
+        if (pos >= 3 * share * a.parts) {                  // this queue is empty: help the next XCD's, until all eight are
             if (++tried == 8) break;
             xcd = (xcd + 1) & 7;
             continue;
         }
-        const int round = pos / share;
-        const int k = corr_item_of_workgroup((pos - round * share) * 8 + xcd);
+        // with parts > 1 consecutive positions are the levels of one item
+        const int part = pos % a.parts, ipos = pos / a.parts;
+        const int round = ipos / share;
+        const int k = corr_item_of_workgroup((ipos - round * share) * 8 + xcd);
         if (k >= n_items) continue;
         const int4 item = a.items[k];
         const int tiles = (item.z + 15) >> 4;
         if ((tiles == 8 ? 0 : tiles >= 5 ? 1 : 2) != round) continue;
+        const int lv_lo = a.parts > 1 ? part : 0, lv_hi = a.parts > 1 ? part + 1 : a.L;
         if (a.r == CORR_R) {
             switch (tiles) {
-                case 1: bwd_item_body<1, MAXK>(a, smem, item, k); break;
-                case 2: bwd_item_body<2, MAXK>(a, smem, item, k); break;
-                case 3: bwd_item_body<3, MAXK>(a, smem, item, k); break;
-                case 4: bwd_item_body<4, MAXK>(a, smem, item, k); break;
-                case 5: bwd_item_body<5, MAXK>(a, smem, item, k); break;
-                case 6: bwd_item_body<6, MAXK>(a, smem, item, k); break;
-                case 7: bwd_item_body<7, MAXK>(a, smem, item, k); break;
-                default: bwd_item_body<8, MAXK>(a, smem, item, k); break;
+                case 1: bwd_item_body<1, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 2: bwd_item_body<2, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 3: bwd_item_body<3, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 4: bwd_item_body<4, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 5: bwd_item_body<5, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 6: bwd_item_body<6, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 7: bwd_item_body<7, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                default: bwd_item_body<8, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
             }
         } else {
             switch (tiles) {
-                case 1: bwd_item_body<1, 0>(a, smem, item, k); break;
-                case 2: bwd_item_body<2, 0>(a, smem, item, k); break;
-                case 3: bwd_item_body<3, 0>(a, smem, item, k); break;
-                case 4: bwd_item_body<4, 0>(a, smem, item, k); break;
-                case 5: bwd_item_body<5, 0>(a, smem, item, k); break;
-                case 6: bwd_item_body<6, 0>(a, smem, item, k); break;
-                case 7: bwd_item_body<7, 0>(a, smem, item, k); break;
-                default: bwd_item_body<8, 0>(a, smem, item, k); break;
+                case 1: bwd_item_body<1, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 2: bwd_item_body<2, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 3: bwd_item_body<3, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 4: bwd_item_body<4, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 5: bwd_item_body<5, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 6: bwd_item_body<6, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                case 7: bwd_item_body<7, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
+                default: bwd_item_body<8, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
             }
         }
     }
@@ -506,6 +512,8 @@ struct GatherArgs {
     const float* d[CORR_MAX_L];
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
     int L, D, W, HW;
+    int parts;                  // d[0] is the sum of this many arrays, part_stride floats apart (d_fmap1 of a small input)
+    size_t part_stride;
 };
 constexpr int TP = 64, TC = 64;
 __global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, float* __restrict__ dst) {
@@ -525,7 +533,12 @@ __global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, floa
                     t = make_float4(v.x + 0.25f * t.x, v.y + 0.25f * t.y, v.z + 0.25f * t.z, v.w + 0.25f * t.w);
                 }
             }
-            const float4 v = *reinterpret_cast<const float4*>(g.d[0] + ((size_t)b * g.HW + p) * g.D + ch);
+            const float* src = g.d[0] + ((size_t)b * g.HW + p) * g.D + ch;
+            float4 v = *reinterpret_cast<const float4*>(src);
+            for (int part = 1; part < g.parts; ++part) {
+                const float4 w = *reinterpret_cast<const float4*>(src + part * g.part_stride);
+                v = make_float4(v.x + w.x, v.y + w.y, v.z + w.z, v.w + w.w);
+            }
             tile[4 * c4 + 0][pr] = v.x + 0.25f * t.x;
             tile[4 * c4 + 1][pr] = v.y + 0.25f * t.y;
             tile[4 * c4 + 2][pr] = v.z + 0.25f * t.z;
@@ -542,10 +555,16 @@ __global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, floa
 
 }  // namespace
 
+// Small inputs run an item's levels in workgroups of their own (a map of a few thousand queries has fewer items
+// than the chip has compute units, and the call's time is one item's latency); each level then adds into a d f1
+// array of its own and the final gather sums them in level order, so the result stays the same bits on every call.
+static int backward_parts(int B, int H, int W, int L) {
+    return (long long)B * H * W <= CORR_SPLIT_LEVELS_MAX_QUERIES ? L : 1;
+}
 size_t corr_backward_workspace_floats(int B, int H, int W, int D, int L) {
     size_t px = 0;
     for (int l = 0; l < L; ++l) px += (size_t)(H >> l) * (W >> l);
-    return ((size_t)B * H * W + (size_t)B * px) * D;
+    return ((size_t)backward_parts(B, H, W, L) * B * H * W + (size_t)B * px) * D;
 }
 
 // gradient arrays (rounded up to 256 bytes), then a planning workspace like the pyramid's (the call bins the
@@ -564,10 +583,13 @@ static long long* g_bwd_trace = nullptr;
 extern "C" void corr_debug_set_backward_trace(long long* p) { g_bwd_trace = p; }
 #endif
 hipError_t launch_backward(const corr_pyramid* p, const float* coords, const float* d_out, int r,
-                           float* d_fmap1, float* d_fmap2, float* ws, int form, hipStream_t s) {
+                           float* d_fmap1, float* d_fmap2, float* ws, int form, int split_max, hipStream_t s) {
     const int HW = p->H * p->W;
     float* cur = ws;
-    float* d_f1 = cur; cur += (size_t)p->B * HW * p->D;
+    // the test hook can lower the size up to which the levels are split (the workspace is laid out for the default)
+    const bool split = split_max < 0 || (long long)p->B * HW <= split_max;
+    const int parts = form == CORR_BACKWARD_ITEMS && split ? backward_parts(p->B, p->H, p->W, p->L) : 1;
+    float* d_f1 = cur; cur += (size_t)backward_parts(p->B, p->H, p->W, p->L) * p->B * HW * p->D;
     float* d_f2[CORR_MAX_L] = {nullptr, nullptr, nullptr, nullptr};
     size_t lev_floats = 0;
     for (int l = 0; l < p->L; ++l) {
@@ -580,7 +602,7 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
     hipError_t e;
     if (form == CORR_BACKWARD_ITEMS) {
         // everything accumulates or keeps its zero (a fill kernel, so the call can be graph-captured)
-        if ((e = launch_fill_i32(reinterpret_cast<int*>(ws), 0, (size_t)p->B * HW * p->D + lev_floats, s)) != hipSuccess) return e;
+        if ((e = launch_fill_i32(reinterpret_cast<int*>(ws), 0, (size_t)(cur - ws), s)) != hipSuccess) return e;
         const BinWs bws = corr_ws_carve(reinterpret_cast<char*>(ws) + grad_bytes(p->B, p->H, p->W, p->D, p->L), (int)BN,
                                         corr_ncells(p->grid, p->B));
         // the bin and item counters start at zero; everything else in the planning workspace is written before it is read
@@ -597,7 +619,7 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
         a.trace = g_bwd_trace;
 #endif
         a.f1 = p->f1_nhwc; a.d_f1 = d_f1; a.d_out = d_out;
-        a.perm = bws.perm; a.sorted_c = bws.sorted_c; a.items = bws.items; a.n_items = bws.n_items; a.queue = reinterpret_cast<int*>(bws.stats);
+        a.perm = bws.perm; a.sorted_c = bws.sorted_c; a.items = bws.items; a.n_items = bws.n_items; a.queue = reinterpret_cast<int*>(bws.stats); a.parts = parts;
         a.B = p->B; a.HW = HW; a.D = p->D; a.L = p->L; a.r = r; a.g = p->grid; a.scale = scale;
         for (int l = 0; l < CORR_MAX_L; ++l) {
             a.f2[l] = l < p->L ? p->f2_nhwc[l] : nullptr; a.d_f2[l] = d_f2[l];
@@ -622,10 +644,11 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
     GatherArgs ga;
     for (int l = 0; l < CORR_MAX_L; ++l) { ga.d[l] = nullptr; ga.Hl[l] = p->Hl[l]; ga.Wl[l] = p->Wl[l]; }
     ga.d[0] = d_f1; ga.L = 1; ga.D = p->D; ga.W = p->W; ga.HW = HW;
+    ga.parts = parts; ga.part_stride = (size_t)p->B * HW * p->D;
     hipLaunchKernelGGL(bwd_gather_nchw_kernel, tg, dim3(256), 0, s, ga, d_fmap1);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     for (int l = 0; l < CORR_MAX_L; ++l) ga.d[l] = d_f2[l];
-    ga.L = p->L;
+    ga.L = p->L; ga.parts = 1;
     hipLaunchKernelGGL(bwd_gather_nchw_kernel, tg, dim3(256), 0, s, ga, d_fmap2);
     return hipGetLastError();
 }

@@ -486,7 +486,7 @@ corr_status corr_sample_backward(const corr_pyramid* pyr, const float* coords, c
     if ((unsigned long long)H * W * D * 4ull >= (1ull << 31)) return CORR_ERR_UNSUPPORTED;
     if ((unsigned long long)H * W * (2 * r + 1) * (2 * r + 1) * 4ull >= (1ull << 31)) return CORR_ERR_UNSUPPORTED;
     const hipError_t e = launch_backward(pyr, coords, d_out, r, d_fmap1, d_fmap2, static_cast<float*>(workspace),
-                                         g_backward_form.load(), static_cast<hipStream_t>(stream));
+                                         g_backward_form.load(), g_split_levels_max.load(), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CORR_OK : CORR_ERR_HIP;
 }
 

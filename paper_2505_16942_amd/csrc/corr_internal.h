@@ -195,6 +195,6 @@ hipError_t launch_ondemand(const corr_pyramid* p, const LookupArgs& q, hipStream
 size_t corr_backward_workspace_floats(int B, int H, int W, int D, int L);      // the gradient arrays
 size_t corr_backward_workspace_bytes_internal(int B, int H, int W, int D, int L);   // those and a planning workspace of its own
 hipError_t launch_backward(const corr_pyramid* p, const float* coords, const float* d_out, int r,
-                           float* d_fmap1, float* d_fmap2, float* ws, int form, hipStream_t s);
+                           float* d_fmap1, float* d_fmap2, float* ws, int form, int split_max, hipStream_t s);
 hipError_t launch_fullvol_build(const corr_pyramid* p, hipStream_t s);
 hipError_t launch_fullvol_sample(const corr_pyramid* p, const LookupArgs& q, hipStream_t s);

@@ -25,19 +25,23 @@ CASES = [
     (2, 40, 60, 64, 4, 4, 9.0),       # 4800 queries: the count + scatter binning path, items of every fill
     (1, 12, 20, 512, 3, 3, 4.0),      # r = 3, two full channel groups
 ]
-FORMS = ["items", "queries"]
+FORMS = ["items", "items, all levels in one workgroup", "queries"]
 
 
 @pytest.fixture(params=FORMS)
 def form(request):
     """Every oracle comparison runs for both kernels behind the entry point: the work-item form on the matrix
-    cores (the default) and the one-wave-per-query form."""
+    cores (the default; with an item's levels split over workgroups, as small inputs run, and in one workgroup,
+    as large ones do) and the one-wave-per-query form."""
     from paper_2505_16942_amd import binding
     binding.load_library()
     prev = binding.corr_debug_set_backward_form(
-        binding.CORR_BACKWARD_ITEMS if request.param == "items" else binding.CORR_BACKWARD_QUERIES)
+        binding.CORR_BACKWARD_QUERIES if request.param == "queries" else binding.CORR_BACKWARD_ITEMS)
+    # small inputs run an item's levels in workgroups of their own; the second form switches that off
+    prev_split = binding.corr_debug_set_level_split(0 if "one workgroup" in request.param else -1)
     yield request.param
     binding.corr_debug_set_backward_form(prev)
+    binding.corr_debug_set_level_split(prev_split)
 
 
 def _binding():
