@@ -508,17 +508,24 @@ __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
 // of parents, evaluated from the deepest level.  With L = 1 this is a plain transposition (d_fmap1).
 // A workgroup moves 64 pixels x 64 channels through LDS: 16-byte loads along the channels (a wave reads four
 // pixels' 256 bytes), 256-byte runs along the pixels on the way out.
-struct GatherArgs {
+struct GatherOne {
     const float* d[CORR_MAX_L];
-    int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
-    int L, D, W, HW;
+    float* dst;
+    int L;                      // levels to fold (1: a plain transposition)
     int parts;                  // d[0] is the sum of this many arrays, part_stride floats apart (d_fmap1 of a small input)
     size_t part_stride;
 };
+struct GatherArgs {
+    GatherOne out[2];           // blockIdx.z = which * B + batch item
+    int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
+    int B, D, W, HW;
+};
 constexpr int TP = 64, TC = 64;
-__global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, float* __restrict__ dst) {
+__global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g) {
     __shared__ float tile[TC][TP + 1];
-    const int b = blockIdx.z, p0 = blockIdx.x * TP, d0 = blockIdx.y * TC;
+    const int which = (int)blockIdx.z / g.B, b = (int)blockIdx.z - which * g.B;
+    const GatherOne& o = g.out[which];
+    const int p0 = blockIdx.x * TP, d0 = blockIdx.y * TC;
 #pragma unroll
     for (int k = 0; k < TP * TC / 4 / 256; ++k) {
         const int idx = threadIdx.x + 256 * k, c4 = idx & (TC / 4 - 1), pr = idx / (TC / 4);
@@ -526,17 +533,17 @@ __global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, floa
         if (p < g.HW && ch < g.D) {                        // D is a multiple of 4
             const int y = p / g.W, x = p - y * g.W;
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int l = g.L - 1; l >= 1; --l) {
+            for (int l = o.L - 1; l >= 1; --l) {
                 const int yy = y >> l, xx = x >> l;
                 if (yy < g.Hl[l] && xx < g.Wl[l]) {
-                    const float4 v = *reinterpret_cast<const float4*>(g.d[l] + (((size_t)b * g.Hl[l] + yy) * g.Wl[l] + xx) * g.D + ch);
+                    const float4 v = *reinterpret_cast<const float4*>(o.d[l] + (((size_t)b * g.Hl[l] + yy) * g.Wl[l] + xx) * g.D + ch);
                     t = make_float4(v.x + 0.25f * t.x, v.y + 0.25f * t.y, v.z + 0.25f * t.z, v.w + 0.25f * t.w);
                 }
             }
-            const float* src = g.d[0] + ((size_t)b * g.HW + p) * g.D + ch;
+            const float* src = o.d[0] + ((size_t)b * g.HW + p) * g.D + ch;
             float4 v = *reinterpret_cast<const float4*>(src);
-            for (int part = 1; part < g.parts; ++part) {
-                const float4 w = *reinterpret_cast<const float4*>(src + part * g.part_stride);
+            for (int part = 1; part < o.parts; ++part) {
+                const float4 w = *reinterpret_cast<const float4*>(src + part * o.part_stride);
                 v = make_float4(v.x + w.x, v.y + w.y, v.z + w.z, v.w + w.w);
             }
             tile[4 * c4 + 0][pr] = v.x + 0.25f * t.x;
@@ -549,7 +556,7 @@ __global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g, floa
 #pragma unroll
     for (int k = 0; k < TP * TC / 256; ++k) {
         const int idx = threadIdx.x + 256 * k, px = idx & (TP - 1), chn = idx / TP;
-        if (d0 + chn < g.D && p0 + px < g.HW) dst[((size_t)b * g.D + d0 + chn) * g.HW + p0 + px] = tile[chn][px];
+        if (d0 + chn < g.D && p0 + px < g.HW) o.dst[((size_t)b * g.D + d0 + chn) * g.HW + p0 + px] = tile[chn][px];
     }
 }
 
@@ -601,14 +608,23 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
     const long long BN = (long long)p->B * HW;
     hipError_t e;
     if (form == CORR_BACKWARD_ITEMS) {
-        // everything accumulates or keeps its zero (a fill kernel, so the call can be graph-captured)
-        if ((e = launch_fill_i32(reinterpret_cast<int*>(ws), 0, (size_t)(cur - ws), s)) != hipSuccess) return e;
-        const BinWs bws = corr_ws_carve(reinterpret_cast<char*>(ws) + grad_bytes(p->B, p->H, p->W, p->D, p->L), (int)BN,
-                                        corr_ncells(p->grid, p->B));
-        // the bin and item counters start at zero; everything else in the planning workspace is written before it is read
-        if ((e = launch_fill_i32(bws.bin_count, 0, (size_t)bws.nbins, s)) != hipSuccess) return e;
-        if ((e = launch_fill_i32(bws.n_items, 0, CORR_NCOUNTERS, s)) != hipSuccess) return e;
-        if ((e = launch_fill_i32(reinterpret_cast<int*>(bws.stats), 0, 8, s)) != hipSuccess) return e;   // the item kernel's queues
+        // Everything accumulates or keeps its zero; in the planning workspace the bin counters, the item counters and
+        // the item kernel's queues (kept in the statistics slots) start at zero, the rest is written before it is
+        // read.  Fill kernels, so the call can be graph-captured.  A small input's whole workspace is cleared in one
+        // launch: there the call's time is launches and one item's latency.
+        const size_t gbytes = grad_bytes(p->B, p->H, p->W, p->D, p->L);
+        const int ncells = corr_ncells(p->grid, p->B);
+        const BinWs bws = corr_ws_carve(reinterpret_cast<char*>(ws) + gbytes, (int)BN, ncells);
+        if (backward_parts(p->B, p->H, p->W, p->L) > 1) {
+            const size_t all = gbytes + corr_ws_layout((int)BN, ncells).total;
+            if ((e = launch_fill_i32(reinterpret_cast<int*>(ws), 0, all / 4, s)) != hipSuccess) return e;
+        } else {
+            if ((e = launch_fill_i32(reinterpret_cast<int*>(ws), 0, (size_t)(cur - ws), s)) != hipSuccess) return e;
+            if ((e = launch_fill_i32(bws.bin_count, 0, (size_t)bws.nbins, s)) != hipSuccess) return e;
+            // item counters and, right behind them, the statistics slots
+            const size_t tail = (size_t)(reinterpret_cast<int*>(bws.stats) + 2 * CORR_NSTATS - bws.n_items);
+            if ((e = launch_fill_i32(bws.n_items, 0, tail, s)) != hipSuccess) return e;
+        }
         LookupArgs q{coords, nullptr, r, 0, 0, 0};
         if ((e = launch_binning(p, bws, q, s)) != hipSuccess) return e;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_item_kernel),
@@ -640,15 +656,16 @@ hipError_t launch_backward(const corr_pyramid* p, const float* coords, const flo
         hipLaunchKernelGGL(bwd_query_kernel, dim3((unsigned)((BN + BQ - 1) / BQ)), dim3(64 * BQ), 0, s, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    dim3 tg((HW + TP - 1) / TP, (p->D + TC - 1) / TC, p->B);
+    // both gradients to NCHW in one launch: d_fmap1 (a small input's per-level shares summed), d_fmap2 (levels folded)
     GatherArgs ga;
-    for (int l = 0; l < CORR_MAX_L; ++l) { ga.d[l] = nullptr; ga.Hl[l] = p->Hl[l]; ga.Wl[l] = p->Wl[l]; }
-    ga.d[0] = d_f1; ga.L = 1; ga.D = p->D; ga.W = p->W; ga.HW = HW;
-    ga.parts = parts; ga.part_stride = (size_t)p->B * HW * p->D;
-    hipLaunchKernelGGL(bwd_gather_nchw_kernel, tg, dim3(256), 0, s, ga, d_fmap1);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    for (int l = 0; l < CORR_MAX_L; ++l) ga.d[l] = d_f2[l];
-    ga.L = p->L; ga.parts = 1;
-    hipLaunchKernelGGL(bwd_gather_nchw_kernel, tg, dim3(256), 0, s, ga, d_fmap2);
+    for (int l = 0; l < CORR_MAX_L; ++l) {
+        ga.Hl[l] = p->Hl[l]; ga.Wl[l] = p->Wl[l];
+        ga.out[0].d[l] = nullptr; ga.out[1].d[l] = d_f2[l];
+    }
+    ga.out[0].d[0] = d_f1; ga.out[0].dst = d_fmap1; ga.out[0].L = 1;
+    ga.out[0].parts = parts; ga.out[0].part_stride = (size_t)p->B * HW * p->D;
+    ga.out[1].dst = d_fmap2; ga.out[1].L = p->L; ga.out[1].parts = 1; ga.out[1].part_stride = 0;
+    ga.B = p->B; ga.D = p->D; ga.W = p->W; ga.HW = HW;
+    hipLaunchKernelGGL(bwd_gather_nchw_kernel, dim3((HW + TP - 1) / TP, (p->D + TC - 1) / TC, 2 * p->B), dim3(256), 0, s, ga);
     return hipGetLastError();
 }
