@@ -185,22 +185,28 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) dst[nt] = buf_load(r_f1, off + ch4 + 64u * nt);
     };
-    auto read_a = [&](int ks, float (&dst)[MT]) {
-        const float* gc = G + lr * GST + 4 * ks + lg;
+    // The point tiles' fragments are 16 rows of G apart (33 * 256 bytes): from a base the compiler has to take as it
+    // is (the empty asm), with constant offsets, two of them leave in one LDS instruction.  Left to itself the loop
+    // optimiser rebases the reads on the end of the range and spends an address addition on every one of them.
+    typedef const __attribute__((address_space(3))) float* lds_cfp;
+    lds_cfp gbase = (lds_cfp)G + lr * GST + lg;
+    auto read_a = [&](lds_cfp gc, float (&dst)[MT]) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) dst[mt] = gc[16 * mt * GST];
     };
     load_b(q_off[lg], bq[0]); load_b(q_off[4 + lg], bq[1]); load_b(q_off[8 + lg], bq[2]);
     unsigned off_next = q_off[12 + lg];
-    read_a(0, af[0]);
+    read_a(gbase, af[0]);
 #pragma unroll 1
     for (int ks0 = 0; ks0 < NMT * 4; ks0 += 4) {
+        lds_cfp gstep = gbase + 4 * ks0;
+        asm volatile("" : "+v"(gstep));
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int ks = ks0 + s;
             load_b(off_next, bq[(s + 3) & 3]);
             off_next = q_off[4 * (ks + 4) + lg];
-            read_a(ks + 1, af[(s + 1) & 1]);
+            read_a(gstep + 4 * (s + 1), af[(s + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
