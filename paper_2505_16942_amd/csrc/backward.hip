@@ -123,7 +123,6 @@ constexpr int NTI = 512;
 constexpr int GST = CORR_GROUP + 4;         // floats between G rows (bank shift 4 per row: a 16-row x 4-query read is conflict-free)
 constexpr int CH = 144;                     // window points per pass: level 2's window in one pass, level 0's in three
 constexpr int MTC = CH / 16;
-constexpr int NTW = 2;                      // 16-channel tiles per wave
 constexpr int TAB_PAD = 16;                 // the operand loads run three k-steps ahead: the tables end in invalid entries
 constexpr int MAXKK = MAXK * MAXK;
 constexpr int ITEM_LDS = CH * GST * 4 + (CH + TAB_PAD) * 4 + (CORR_GROUP + TAB_PAD) * 4 + CORR_GROUP * 8 + MAXKK * CORR_GROUP * 4;
@@ -171,7 +170,7 @@ __device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, unsigned off
 // atomics.  k-step ks takes queries 4*ks + lg.  Software pipeline, pinned by the scheduling barriers: the f1 values
 // of step ks + 3, the table entry of step ks + 4 and the G fragments of step ks + 1 are on their way while the
 // matrix cores work on step ks.
-template <int NMT, int MT>
+template <int NMT, int MT, int NTW>
 __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* rowoff, const unsigned* q_off,
                                               __amdgpu_buffer_rsrc_t r_f1, __amdgpu_buffer_rsrc_t r_d2,
                                               unsigned ch4, int lr, int lg) {
@@ -237,7 +236,9 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
 #define BT(slot) do {} while (0)
 #endif
 // KT: the window side 2r + 1 as a constant (the largest radius, the usual one), or 0: taken from the arguments
-template <int NMT, int KT>
+// NTW: 16-channel tiles per wave: 2 (a workgroup covers 256 channels at a time), or 1 for D <= 128, so that all
+// eight waves have channels to work on
+template <int NMT, int KT, int NTW>
 __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned char* smem, const int4 item, const int k,
                                               const int lv_lo, const int lv_hi, const int part) {
     float* G = reinterpret_cast<float*>(smem);                   // [CH][GST]
@@ -272,7 +273,7 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
     const __amdgpu_buffer_rsrc_t r_f1 = rsrc_of(a.f1 + (size_t)b * a.HW * D, (size_t)a.HW * D);
     const __amdgpu_buffer_rsrc_t r_d1 = rsrc_of(a.d_f1 + ((size_t)part * a.B + b) * a.HW * D, (size_t)a.HW * D);
 
-    for (int cg = 0; cg < D; cg += 256) {                        // channel groups of 256: 32 per wave
+    for (int cg = 0; cg < D; cg += 128 * NTW) {                  // channel groups of 128 * NTW: 16 * NTW per wave
         const int ch = cg + wave * (16 * NTW) + lr;              // this lane's channel of tile nt: ch + 16 * nt
         const bool wave_on = cg + wave * (16 * NTW) < D;         // uniform; D is a multiple of 32
         f32x4 acc1[NMT][NTW];
@@ -420,10 +421,10 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
                     const unsigned ch4 = (unsigned)ch * 4u;
                     // d f2_l rows of this pass = G x f1, over as many 16-point tiles as the pass has rows (rounded up to odd)
                     const int tiles = (rows + 15) >> 4;
-                    if (tiles <= 3) rows_gradient<NMT, 3>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
-                    else if (tiles <= 5) rows_gradient<NMT, 5>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
-                    else if (tiles <= 7) rows_gradient<NMT, 7>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
-                    else rows_gradient<NMT, MTC>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
+                    if (tiles <= 3) rows_gradient<NMT, 3, NTW>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
+                    else if (tiles <= 5) rows_gradient<NMT, 5, NTW>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
+                    else if (tiles <= 7) rows_gradient<NMT, 7, NTW>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
+                    else rows_gradient<NMT, MTC, NTW>(G, rowoff, q_off, r_f1, r_d2, ch4, lr, lg);
                 }
                 BT(5);
             }
@@ -481,29 +482,20 @@ __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
         const int tiles = (item.z + 15) >> 4;
         if ((tiles == 8 ? 0 : tiles >= 5 ? 1 : 2) != round) continue;
         const int lv_lo = a.parts > 1 ? part : 0, lv_hi = a.parts > 1 ? part + 1 : a.L;
-        if (a.r == CORR_R) {
-            switch (tiles) {
-                case 1: bwd_item_body<1, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 2: bwd_item_body<2, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 3: bwd_item_body<3, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 4: bwd_item_body<4, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 5: bwd_item_body<5, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 6: bwd_item_body<6, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 7: bwd_item_body<7, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                default: bwd_item_body<8, MAXK>(a, smem, item, k, lv_lo, lv_hi, part); break;
-            }
-        } else {
-            switch (tiles) {
-                case 1: bwd_item_body<1, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 2: bwd_item_body<2, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 3: bwd_item_body<3, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 4: bwd_item_body<4, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 5: bwd_item_body<5, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 6: bwd_item_body<6, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                case 7: bwd_item_body<7, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-                default: bwd_item_body<8, 0>(a, smem, item, k, lv_lo, lv_hi, part); break;
-            }
+#define CORR_BWD_CASE(N, KT, NTW) case N: bwd_item_body<N, KT, NTW>(a, smem, item, k, lv_lo, lv_hi, part); break;
+#define CORR_BWD_SWITCH(KT, NTW)                                                                              \
+        switch (tiles) {                                                                                      \
+            CORR_BWD_CASE(1, KT, NTW) CORR_BWD_CASE(2, KT, NTW) CORR_BWD_CASE(3, KT, NTW) CORR_BWD_CASE(4, KT, NTW) \
+            CORR_BWD_CASE(5, KT, NTW) CORR_BWD_CASE(6, KT, NTW) CORR_BWD_CASE(7, KT, NTW)                     \
+            default: bwd_item_body<8, KT, NTW>(a, smem, item, k, lv_lo, lv_hi, part); break;                  \
         }
+        if (a.D <= 128) {
+            if (a.r == CORR_R) { CORR_BWD_SWITCH(MAXK, 1) } else { CORR_BWD_SWITCH(0, 1) }
+        } else {
+            if (a.r == CORR_R) { CORR_BWD_SWITCH(MAXK, 2) } else { CORR_BWD_SWITCH(0, 2) }
+        }
+#undef CORR_BWD_SWITCH
+#undef CORR_BWD_CASE
     }
 }
 

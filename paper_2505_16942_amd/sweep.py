@@ -23,7 +23,9 @@ width at which block mode overtakes it in this table flatters block mode; the me
 depend on that.
 
 Usage (GPU machine, repository root):  python -m paper_2505_16942_amd.sweep [--quick]
-Prints a markdown table.
+Prints a markdown table.  With --backward it prints a second kind of table instead: one call of the lookup's
+gradient (corr_sample_backward) over the same widths and feature dimensionalities, in both of its forms, beside one
+lookup.
 """
 from __future__ import annotations
 
@@ -104,9 +106,44 @@ def _run_point(width: int, iters: int, D: int, L: int = 4, r: int = 4, reps_time
     return H, W, res
 
 
+def _backward_point(width: int, D: int, calls: int = 5):
+    """(H, W, ms of one lookup, ms of one gradient call in the work-item form, ms in the one-wave-per-query form)."""
+    import torch
+    from . import binding as cb
+    H, W, f1, f2, cs = _case(width, D, 11)
+    dev = f1.device
+    d_out = torch.randn((1, 4 * 81, H, W), device=dev)
+    pyr = cb.corr_pyramid_build(f1, f2, L=4, reps=cb.CORR_REP_F32 | cb.CORR_REP_SPLIT)
+    ws = torch.empty(cb.corr_backward_workspace_bytes(1, H, W, D, 4) // 4, device=dev)
+    g1, g2 = torch.empty_like(f1), torch.empty_like(f1)
+    out = cb.corr_sample(f1, pyr, cs[0])
+
+    def timed(fn, n):
+        fn(); fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    res = [timed(lambda: cb.corr_sample(f1, pyr, cs[0], out=out), calls)]
+    try:
+        for form, n in ((cb.CORR_BACKWARD_ITEMS, calls), (cb.CORR_BACKWARD_QUERIES, 2)):
+            cb.corr_debug_set_backward_form(form)
+            res.append(timed(lambda: cb.corr_sample_backward(pyr, cs[0], d_out, d_fmap1=g1, d_fmap2=g2, workspace=ws), n))
+    finally:
+        cb.corr_debug_set_backward_form(cb.CORR_BACKWARD_ITEMS)
+    pyr.destroy()
+    return H, W, res[0], res[1], res[2]
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--quick", action="store_true", help="fewer and smaller points")
+    ap.add_argument("--backward", action="store_true", help="the gradient's table instead of the lookup's")
     args = ap.parse_args(argv)
     import torch
     from . import binding as cb
@@ -114,6 +151,15 @@ def main(argv=None) -> int:
         print("sweep: no GPU visible", file=sys.stderr)
         return 1
     cb.load_library()
+    if args.backward:
+        pts = [("Input width", w, (w, 256)) for w in ((32, 128, 512) if args.quick else (32, 64, 128, 256, 512, 1024))]
+        pts += [("Feature dimensionality", d, (512, d)) for d in ((64,) if args.quick else (64, 128, 512))]
+        print("| variable | value | map HxW | one lookup (block bf16x3) ms | gradient, work items ms | gradient, one wave per query ms |")
+        print("|---|---|---|---|---|---|")
+        for var, val, (w, d) in pts:
+            H, W, fwd, items, queries = _backward_point(w, d)
+            print("| %s | %d | %dx%d | %.3f | %.3f | %.3f |" % (var, val, H, W, fwd, items, queries), flush=True)
+        return 0
     base_w, base_it, base_d = 512, 32, 256
     if args.quick:
         points = [("Input width", w, (w, base_it, base_d)) for w in (32, 128, 512)]
