@@ -151,6 +151,56 @@ def test_the_two_forms_agree_at_benchmark_sizes(cfg_name, r):
     pyr.destroy()
 
 
+def test_backward_replayed_from_a_hip_graph():
+    """corr_sample_backward allocates nothing and clears what it accumulates into with kernels, so a caller may
+    capture it (here two calls with different coordinates); every replay must give the eager d_fmap1 bit for bit and
+    the eager d_fmap2 to rounding (its atomics are unordered), also with the program's own eager call in between."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 1, 30, 44, 64, 4
+    f1, f2, c0 = synth.small_case(61, B, H, W, D, flow_range=9.0)
+    _, _, c1 = synth.small_case(62, B, H, W, D, flow_range=9.0)
+    t1, t2 = torch.from_numpy(f1).to(dev), torch.from_numpy(f2).to(dev)
+    tcs = [torch.from_numpy(c0).to(dev), torch.from_numpy(c1).to(dev)]
+    gen = torch.Generator(device=dev); gen.manual_seed(3)
+    d_out = torch.randn((B, L * 81, H, W), device=dev, generator=gen)
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_F32)
+    ws = torch.empty(b.corr_backward_workspace_bytes(B, H, W, D, L) // 4, device=dev)
+    g1 = [torch.empty_like(t1) for _ in range(2)]
+    g2 = [torch.empty_like(t1) for _ in range(2)]
+
+    def job():
+        for t in range(2):
+            b.corr_sample_backward(pyr, tcs[t], d_out, d_fmap1=g1[t], d_fmap2=g2[t], workspace=ws)
+
+    job()
+    torch.cuda.synchronize()
+    e1, e2 = [x.clone() for x in g1], [x.clone() for x in g2]
+    want = oracle.backward(f1, f2, c0, d_out.cpu().numpy(), L=L, r=4)
+    _check(e1[0], want[0], "eager d_fmap1")
+    _check(e2[0], want[1], "eager d_fmap2")
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            job()
+    torch.cuda.synchronize()
+    tol2 = 1e-5 * float(e2[0].abs().max())
+    for rep in range(4):
+        for x in g1 + g2:
+            x.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for t in range(2):
+            assert torch.equal(g1[t], e1[t]), "replay %d, d_fmap1 of call %d" % (rep, t)
+            assert float((g2[t] - e2[t]).abs().max()) <= tol2, "replay %d, d_fmap2 of call %d" % (rep, t)
+        b.corr_sample_backward(pyr, tcs[1], d_out, d_fmap1=g1[0], d_fmap2=g2[0], workspace=ws)   # eager work in between
+        torch.cuda.synchronize()
+        assert torch.equal(g1[0], e1[1])
+    pyr.destroy()
+
+
 def test_backward_leaves_the_pyramids_plan_alone():
     """The gradient bins the queries in its own workspace: a lookup's plan in the pyramid (read back through the
     test hook) is the same before and after a backward call with other coordinates."""
