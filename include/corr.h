@@ -133,7 +133,8 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
  *               pooling dropped receives level 0's share only).
  *   workspace : device, at least corr_backward_workspace_bytes(B, H, W, D, L) bytes, 16-byte aligned
  *               (else CORR_ERR_INVALID_ARG), caller-owned; contents on entry are ignored, contents on return
- *               are scratch.  It holds the channels-last gradients of fmap1 and of every level and a planning
+ *               are scratch.  It holds the channels-last gradients of fmap1 (one array per level for inputs of
+ *               up to 32000 queries) and of every level of fmap2, and a planning
  *               workspace of the call's own: the pyramid is only read, so the call may run beside lookups
  *               on the same pyramid.
  * Enqueues kernels on `stream` and returns; allocates nothing.  The queries are binned into the forward
