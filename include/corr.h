@@ -134,12 +134,12 @@ corr_status corr_sample_mode(corr_mode mode, corr_precision prec,
  *   workspace : device, at least corr_backward_workspace_bytes(B, H, W, D, L) bytes, 16-byte aligned
  *               (else CORR_ERR_INVALID_ARG), caller-owned; contents on entry are ignored, contents on return
  *               are scratch.  It holds the channels-last gradients of fmap1 (one array per level for inputs of
- *               up to 32000 queries) and of every level of fmap2, and a planning
+ *               up to 32000 queries, two up to 40000) and of every level of fmap2, and a planning
  *               workspace of the call's own: the pyramid is only read, so the call may run beside lookups
  *               on the same pyramid.
  * Enqueues kernels on `stream` and returns; allocates nothing.  The queries are binned into the forward
  * pass's work items (a target cell and up to 128 of its queries); per item and level both gradients are
- * fp32 matrix-core contractions over the item's window (inputs of up to 32000 queries run an item's levels
+ * fp32 matrix-core contractions over the item's window (inputs of up to 40000 queries run an item's levels
  * in workgroups of their own and sum their shares of d_fmap1 in level order).  fp32 throughout.  d_fmap1 has the same bits on
  * every call; d_fmap2 is accumulated with floating-point atomics, so two calls agree to rounding, not bit
  * for bit.  Limits beyond corr_sample's: H*W*D*4 and H*W*(2r+1)^2*4 below 2^31 (one batch item's map and

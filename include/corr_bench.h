@@ -83,7 +83,7 @@ corr_status corr_debug_read_plan(const corr_pyramid* pyr, int32_t* counts, int32
  * enough: four ways up to 64 items, two ways up to 384, else all levels in one workgroup).  0 = never (the
  * one-workgroup-per-item kernel that large inputs take), -1 restores the default (32000), -2 / -4 = always two / four ways, whatever the size.  All forms give the same bits.
  * Returns the previous setting.  Not synchronised with lookups in flight on other threads.
- * corr_sample_backward splits an item's levels over workgroups up to a size of its own (32000 queries as well); a setting
+ * corr_sample_backward splits an item's levels over workgroups up to sizes of its own (all levels apart up to 32000 queries, level 0 apart up to 40000); a setting
  * of 0 switches that off, every other setting leaves the gradient at its default.
  */
 int corr_debug_set_level_split(int max_queries);

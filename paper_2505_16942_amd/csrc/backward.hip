@@ -139,7 +139,7 @@ struct BwdItemArgs {
     const int4* items;
     const int* n_items;
     int* queue;                             // [8] next queue position per XCD, zero on entry
-    int parts;                              // 1, or L: small inputs run an item's levels in workgroups of their own, each with
+    int parts;                              // 1, 2 or L: small inputs run an item's levels in workgroups of their own, each with
                                             // a d_f1 array of its own (part p at d_f1 + p * B*HW*D), summed in order at the end
     int B, HW, D, L, r;
     int Hl[CORR_MAX_L], Wl[CORR_MAX_L];
@@ -481,7 +481,9 @@ __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
         const int4 item = a.items[k];
         const int tiles = (item.z + 15) >> 4;
         if ((tiles == 8 ? 0 : tiles >= 5 ? 1 : 2) != round) continue;
-        const int lv_lo = a.parts > 1 ? part : 0, lv_hi = a.parts > 1 ? part + 1 : a.L;
+        // parts = L: one level each; parts = 2 (and L > 2): level 0, and the rest
+        const int lv_lo = a.parts > 1 ? part : 0;
+        const int lv_hi = a.parts == 1 || (a.parts == 2 && part == 1) ? a.L : part + 1;
 #define CORR_BWD_CASE(N, KT, NTW) case N: bwd_item_body<N, KT, NTW>(a, smem, item, k, lv_lo, lv_hi, part); break;
 #define CORR_BWD_SWITCH(KT, NTW)                                                                              \
         switch (tiles) {                                                                                      \
@@ -566,8 +568,12 @@ __global__ __launch_bounds__(256) void bwd_gather_nchw_kernel(GatherArgs g) {
 #ifndef CORR_BACKWARD_SPLIT_MAX_QUERIES
 #define CORR_BACKWARD_SPLIT_MAX_QUERIES 32000   // measured: the split gains up to about 28000 queries and costs 8 % at 45000
 #endif
+#ifndef CORR_BACKWARD_HALVE_MAX_QUERIES
+#define CORR_BACKWARD_HALVE_MAX_QUERIES 40000   // up to here an item is two pieces: level 0 (three passes) and the other levels (four); measured: -7 % at 32400 queries, nothing from 45000 on
+#endif
 static int backward_parts(int B, int H, int W, int L) {
-    return (long long)B * H * W <= CORR_BACKWARD_SPLIT_MAX_QUERIES ? L : 1;
+    const long long BN = (long long)B * H * W;
+    return BN <= CORR_BACKWARD_SPLIT_MAX_QUERIES ? L : (BN <= CORR_BACKWARD_HALVE_MAX_QUERIES && L > 1) ? 2 : 1;
 }
 size_t corr_backward_workspace_floats(int B, int H, int W, int D, int L) {
     size_t px = 0;
