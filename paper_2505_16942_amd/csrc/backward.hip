@@ -450,37 +450,34 @@ __device__ __forceinline__ void bwd_item_body(const BwdItemArgs& a, unsigned cha
 }
 
 // One workgroup per compute unit, each taking items from a queue until it is empty.  Workgroup w runs on XCD
-// w % 8 and serves that XCD's share of the item list (runs of CORR_XCD_RUN consecutive items, as in the forward
-// kernel: neighbouring cells share window rows, so they should share an L2).  A queue goes over its share three
-// times and each time hands out one class of items: the full ones, the middle ones, the small ones (a workgroup
-// whose queue has run out goes on with the next XCD's).  The long
-// items so start first and the short ones fill the end of the launch, and no compute unit spends time on
-// workgroups that find nothing to do (one of this kernel's workgroups needs most of a unit's LDS, so even an
-// empty one waits for a unit of its own).
+// w % 8 and serves that XCD's share of the item list in list order (runs of CORR_XCD_RUN consecutive items, as in
+// the forward kernel: neighbouring cells share window rows, so they should share an L2 and run at about the same
+// time); a workgroup whose queue has run out goes on with the next XCD's.  So no compute unit spends time on
+// workgroups that find nothing to do (one of this kernel's workgroups needs most of a unit's LDS, so even an empty
+// one waits for a unit of its own), and the end of the launch is shared out item by item.  Handing out the full
+// items first and the small ones last was measured too: it costs more in L2 misses than it gains at the end.
 __global__ __launch_bounds__(NTI, 2) void bwd_item_kernel(BwdItemArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_next;
     int xcd = (int)blockIdx.x & 7, tried = 0;
     const int n_items = *a.n_items;
-    const int share = (n_items + 8 * CORR_XCD_RUN - 1) / (8 * CORR_XCD_RUN) * CORR_XCD_RUN;   // queue positions per round
+    const int share = (n_items + 8 * CORR_XCD_RUN - 1) / (8 * CORR_XCD_RUN) * CORR_XCD_RUN;   // item positions per queue
     for (;;) {
         __syncthreads();                                   // the previous item's last LDS reads; s_next has been read
         if (threadIdx.x == 0) s_next = atomicAdd(a.queue + xcd, 1);
         __syncthreads();
         const int pos = s_next;                            // uniform
-        if (pos >= 3 * share * a.parts) {                  // this queue is empty: help the next XCD's, until all eight are
+        if (pos >= share * a.parts) {                  // this queue is empty: help the next XCD's, until all eight are
             if (++tried == 8) break;
             xcd = (xcd + 1) & 7;
             continue;
         }
         // with parts > 1 consecutive positions are the levels of one item
         const int part = pos % a.parts, ipos = pos / a.parts;
-        const int round = ipos / share;
-        const int k = corr_item_of_workgroup((ipos - round * share) * 8 + xcd);
+        const int k = corr_item_of_workgroup(ipos * 8 + xcd);
         if (k >= n_items) continue;
         const int4 item = a.items[k];
         const int tiles = (item.z + 15) >> 4;
-        if ((tiles == 8 ? 0 : tiles >= 5 ? 1 : 2) != round) continue;
         // parts = L: one level each; parts = 2 (and L > 2): level 0, and the rest
         const int lv_lo = a.parts > 1 ? part : 0;
         const int lv_hi = a.parts == 1 || (a.parts == 2 && part == 1) ? a.L : part + 1;
