@@ -116,8 +116,8 @@ __global__ __launch_bounds__(64 * BQ) void bwd_query_kernel(BwdArgs a) {
 // CH points at a time from the tap gradients (a footprint point collects up to four taps); d f1 stays in
 // accumulators over all levels and is stored once (a query belongs to one item); the window's d f2_l rows go
 // out through float atomics once per item and pass, instead of once per query and footprint point.
-// Eight waves, two per SIMD: a wave owns 32 channels of a 256-channel group; lane = (K index lane/16, M or N
-// index lane%16).  Feature rows come through buffer resources: an offset past the end reads zero and an atomic
+// Eight waves, two per SIMD: a wave owns 32 channels of a 256-channel group (16 of a 128-channel group for
+// D <= 128); lane = (K index lane/16, M or N index lane%16).  Feature rows come through buffer resources: an offset past the end reads zero and an atomic
 // there is dropped, so rows outside the level and empty query slots need no branch inside the loops.
 constexpr int NTI = 512;
 constexpr int GST = CORR_GROUP + 4;         // floats between G rows (bank shift 4 per row: a 16-row x 4-query read is conflict-free)
@@ -227,14 +227,15 @@ __device__ __forceinline__ void rows_gradient(const float* G, const unsigned* ro
     }
 }
 
-// NMT: 16-query tiles the item fills (1..8)
 #ifdef CORR_TRACE
 // trace builds: thread 0 adds up the 100 MHz wall clock per phase (a barrier in front of every reading, so a phase's
-// time is that of its slowest wave) and leaves the item's seven sums and its tile count in trace[workgroup][8]
+// time is that of its slowest wave) and leaves the item's seven sums and its tile count in trace[item][8]
 #define BT(slot) do { __builtin_amdgcn_s_barrier(); if (tid == 0) { long long now = (long long)wall_clock64(); tacc[slot] += now - tlast; tlast = now; } } while (0)
 #else
 #define BT(slot) do {} while (0)
 #endif
+// One item, levels lv_lo .. lv_hi - 1, d f1 into share `part` (whole items: all levels, share 0).
+// NMT: 16-query tiles the item fills (1..8)
 // KT: the window side 2r + 1 as a constant (the largest radius, the usual one), or 0: taken from the arguments
 // NTW: 16-channel tiles per wave: 2 (a workgroup covers 256 channels at a time), or 1 for D <= 128, so that all
 // eight waves have channels to work on
