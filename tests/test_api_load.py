@@ -99,3 +99,21 @@ def test_every_work_item_has_exactly_one_workgroup():
     xcd_of_item[m] = np.arange(grid) % 8
     assert np.all(xcd_of_item.reshape(-1, 32) == xcd_of_item.reshape(-1, 32)[:, :1])
     assert np.array_equal(xcd_of_item.reshape(-1, 32)[:8, 0], np.arange(8))
+
+
+def test_backward_workspace_bytes():
+    """Host arithmetic only: the gradient's workspace holds the channels-last gradient of fmap1 (one array per level
+    up to 32000 queries, two up to 40000, one beyond), of every level of fmap2, and a planning workspace that is
+    linear in pixels and small."""
+    binding, _ = _lib()
+
+    def grad_floats(B, H, W, D, L, parts):
+        return (parts * B * H * W + B * sum((H >> l) * (W >> l) for l in range(L))) * D
+
+    for (B, H, W, D, L, parts) in [(1, 30, 44, 64, 4, 4), (2, 100, 160, 256, 4, 4), (1, 135, 240, 256, 4, 2),
+                                   (1, 135, 240, 256, 1, 1), (1, 270, 480, 256, 4, 1), (1, 540, 960, 256, 3, 1)]:
+        need = binding.corr_backward_workspace_bytes(B, H, W, D, L)
+        g = 4 * grad_floats(B, H, W, D, L, parts)
+        plan = need - g
+        assert need % 256 == 0
+        assert 0 < plan < 256 + 64 * B * H * W + (1 << 20), (B, H, W, D, L, need, g)
