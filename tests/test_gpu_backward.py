@@ -201,6 +201,34 @@ def test_backward_replayed_from_a_hip_graph():
     pyr.destroy()
 
 
+@pytest.mark.parametrize("fill", ["nan", "far"])
+def test_no_query_in_range_gives_zero_gradients(fill, form):
+    """Coordinates that are all non-finite or far outside every level: the lookup is the constant 0, so both
+    gradients are exactly 0 (no item exists; the outputs are still fully written)."""
+    b = _binding()
+    dev = torch.device("cuda:0")
+    B, H, W, D, L = 2, 20, 28, 64, 4
+    f1, f2, c = synth.small_case(81, B, H, W, D)
+    t1, t2 = torch.from_numpy(f1).to(dev), torch.from_numpy(f2).to(dev)
+    bad = torch.full((B, 2, H, W), float("nan") if fill == "nan" else 5000.0, device=dev)
+    d_out = torch.ones((B, L * 81, H, W), device=dev)
+    pyr = b.corr_pyramid_build(t1, t2, L=L, reps=b.CORR_REP_F32)
+    g1 = torch.full((B, D, H, W), float("nan"), device=dev)
+    g2 = torch.full((B, D, H, W), float("nan"), device=dev)
+    b.corr_sample_backward(pyr, bad, d_out, d_fmap1=g1, d_fmap2=g2)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(g1).item() == 0 and torch.count_nonzero(g2).item() == 0
+    assert not torch.isnan(g1).any() and not torch.isnan(g2).any()
+    # and a normal call afterwards is unaffected
+    tc = torch.from_numpy(c).to(dev)
+    want = oracle.backward(f1, f2, c, d_out.cpu().numpy(), L=L, r=4)
+    h1, h2 = b.corr_sample_backward(pyr, tc, d_out)
+    torch.cuda.synchronize()
+    _check(h1, want[0], "d_fmap1 after an empty call")
+    _check(h2, want[1], "d_fmap2 after an empty call")
+    pyr.destroy()
+
+
 def test_backward_leaves_the_pyramids_plan_alone():
     """The gradient bins the queries in its own workspace: a lookup's plan in the pyramid (read back through the
     test hook) is the same before and after a backward call with other coordinates."""
