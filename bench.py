@@ -87,7 +87,7 @@ def bench_backward(args, cb, synth, torch, np) -> int:
                         "%.0f G/s here" % (atomics, atomics / dt / 1e9)}
     result = {
         "metric": "correlation lookup gradient, tap gradients/s (queries x L x 81 taps)", "value": taps / dt,
-        "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
+        "unit": "tap gradients/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: B=%d fmap [%d,%d,%d,%d] L=%d r=%d; step = one corr_sample_backward (%s form)"
                                % (args.config, B, B, D, H, W, L, r, args.backward_form), "seed": cfg["seed"]},
