@@ -24,6 +24,7 @@ CASES = [
     (1, 13, 17, 320, 4, 1, 5.0),      # r = 1, five channel slots per lane; a second, partly filled channel group
     (2, 40, 60, 64, 4, 4, 9.0),       # 4800 queries: the count + scatter binning path, items of every fill
     (1, 12, 20, 512, 3, 3, 4.0),      # r = 3, two full channel groups
+    (1, 10, 14, 32, 1, 4, 3.0),       # a single level
 ]
 FORMS = ["items", "items, all levels in one workgroup", "queries"]
 
